@@ -1,0 +1,208 @@
+"""CPU oracle of the DASGD/SGNS worker step -- TEST INFRASTRUCTURE ONLY.
+
+``tensair_oracle.c`` is the plain sequential statement of the step (double
+arithmetic); this module builds it with gcc and wraps it with ctypes/numpy.
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import it.  It imports nothing from the product package.
+
+Paper: TensAIR, arXiv 2211.10280 -- Eq. 1, Algorithm 1 (train), Section 3.1
+(staleness and ordering), Section 4 (sparse updates).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tensair_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+F32, BF16, F64 = 0, 1, 2
+_NP = {F32: np.float32, BF16: np.uint16, F64: np.float64}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add contraction, so the
+    single-precision initialisation is evaluated exactly as written)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, i32, i64, u32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64
+        L.orc_philox4x32_10.argtypes = [vp, vp, vp]
+        L.orc_philox4x32_10.restype = None
+        L.orc_alias_build.argtypes = [vp, i64, vp, vp]
+        L.orc_alias_build.restype = C.c_int
+        L.orc_pairs.argtypes = [i64, i32, i64, i32, vp, vp]
+        L.orc_pairs.restype = i64
+        L.orc_sample_negatives.argtypes = [i64, vp, vp, u64, u32, u32, i64, vp, vp, i32, vp]
+        L.orc_sample_negatives.restype = None
+        L.orc_init_tables.argtypes = [i64, i32, i32, C.c_int, u64, vp, vp]
+        L.orc_init_tables.restype = None
+        L.orc_sgns_grad.argtypes = [vp, i64, i32, i32, i64, i32, i64, i32, i32, C.c_int,
+                                    vp, vp, vp, vp, u64, u32, u32, vp]
+        L.orc_sgns_grad.restype = vp
+        L.orc_grad_sizes.argtypes = [vp, vp, vp, vp]
+        L.orc_grad_sizes.restype = None
+        L.orc_grad_loss.argtypes = [vp]
+        L.orc_grad_loss.restype = C.c_double
+        L.orc_grad_export.argtypes = [vp] * 10
+        L.orc_grad_export.restype = None
+        L.orc_grad_free.argtypes = [vp]
+        L.orc_grad_free.restype = None
+        L.orc_dasgd_apply_table.argtypes = [i64, i32, i32, C.c_int, vp, i32, vp, vp, vp, C.c_float]
+        L.orc_dasgd_apply_table.restype = None
+        L.orc_double_to_bf16.argtypes = [C.c_double]
+        L.orc_double_to_bf16.restype = C.c_uint16
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+# ---------------------------------------------------------------- primitives
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def alias_build(counts):
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    V = counts.shape[0]
+    thr = np.zeros(V, dtype=np.uint32)
+    alias = np.zeros(V, dtype=np.int32)
+    rc = lib().orc_alias_build(_p(counts), V, _p(thr), _p(alias))
+    if rc != 0:
+        raise ValueError("alias_build: no id has a positive count")
+    return thr, alias
+
+
+def pairs(T, w, begin, n):
+    P = lib().orc_pairs(T, w, begin, n, None, None)
+    pos = np.zeros(max(P, 1), dtype=np.int64)
+    q = np.zeros(max(P, 1), dtype=np.int32)
+    lib().orc_pairs(T, w, begin, n, _p(pos), _p(q))
+    return pos[:P], q[:P]
+
+
+def sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N):
+    pos = np.ascontiguousarray(pos, dtype=np.int64)
+    q = np.ascontiguousarray(q, dtype=np.int32)
+    P = pos.shape[0]
+    out = np.zeros((P, N), dtype=np.int32)
+    lib().orc_sample_negatives(V, _p(thr), _p(alias), seed, worker, epoch, P, _p(pos), _p(q), N, _p(out))
+    return out
+
+
+def double_to_bf16(x: float) -> int:
+    return int(lib().orc_double_to_bf16(float(x)))
+
+
+def bf16_to_f32(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32)
+
+
+def init_tables(V, D, stride, dtype, seed):
+    w_in = np.zeros((V, stride), dtype=_NP[dtype])
+    w_out = np.zeros((V, stride), dtype=_NP[dtype])
+    lib().orc_init_tables(V, D, stride, dtype, seed, _p(w_in), _p(w_out))
+    return w_in, w_out
+
+
+# ---------------------------------------------------------------- gradient
+@dataclass
+class SparseRows:
+    ids: np.ndarray      # int32 [U] ascending unique
+    rows: np.ndarray     # float32 [U, D]
+    seg: np.ndarray      # int64 [U+1] occurrence offsets
+    rows64: np.ndarray | None = None
+
+
+@dataclass
+class Grad:
+    P: int
+    loss: float
+    negatives: np.ndarray   # int32 [P, N]
+    gin: SparseRows
+    gout: SparseRows
+
+
+def sgns_grad(tok, w, N, begin, n_centers, D, dtype, W_in, W_out, thr, alias,
+              seed, worker, epoch, neg_override=None, want64=False) -> Grad:
+    """calculate_gradient of Algorithm 1 for one mini-batch of centers."""
+    tok = np.ascontiguousarray(tok, dtype=np.int32)
+    T = tok.shape[0]
+    V, stride = W_in.shape
+    assert W_in.dtype == _NP[dtype] and W_out.dtype == _NP[dtype]
+    assert W_in.flags.c_contiguous and W_out.flags.c_contiguous
+    if neg_override is not None:
+        neg_override = np.ascontiguousarray(neg_override, dtype=np.int32)
+    L = lib()
+    h = L.orc_sgns_grad(_p(tok), T, w, N, begin, n_centers, V, D, stride, dtype,
+                        _p(W_in), _p(W_out), _p(thr), _p(alias), seed, worker, epoch,
+                        _p(neg_override))
+    try:
+        P, Ui, Uo = C.c_int64(), C.c_int64(), C.c_int64()
+        L.orc_grad_sizes(h, C.byref(P), C.byref(Ui), C.byref(Uo))
+        P, Ui, Uo = P.value, Ui.value, Uo.value
+        gi = SparseRows(np.zeros(Ui, np.int32), np.zeros((Ui, D), np.float32), np.zeros(Ui + 1, np.int64),
+                        np.zeros((Ui, D), np.float64) if want64 else None)
+        go = SparseRows(np.zeros(Uo, np.int32), np.zeros((Uo, D), np.float32), np.zeros(Uo + 1, np.int64),
+                        np.zeros((Uo, D), np.float64) if want64 else None)
+        neg = np.zeros((P, N), dtype=np.int32)
+        L.orc_grad_export(h, _p(gi.ids), _p(gi.rows), _p(gi.rows64), _p(gi.seg),
+                          _p(go.ids), _p(go.rows), _p(go.rows64), _p(go.seg), _p(neg))
+        loss = L.orc_grad_loss(h)
+    finally:
+        L.orc_grad_free(h)
+    return Grad(P, loss, neg, gi, go)
+
+
+# ---------------------------------------------------------------- apply
+def dasgd_apply_table(W, D, dtype, sources, lr):
+    """apply_gradient of Algorithm 1 / Eq. 1 on one table, in place.
+    ``sources`` = list of (ids int32[U_k], rows float32[U_k, D]); source 0 is the own
+    gradient, the others are peers' (same alpha, summed)."""
+    V, stride = W.shape
+    assert W.dtype == _NP[dtype] and W.flags.c_contiguous
+    K = len(sources)
+    ids = [np.ascontiguousarray(s[0], dtype=np.int32) for s in sources]
+    rows = [np.ascontiguousarray(s[1], dtype=np.float32) for s in sources]
+    n = np.array([i.shape[0] for i in ids], dtype=np.int64)
+    idp = (C.c_void_p * max(K, 1))(*[i.ctypes.data for i in ids])
+    rwp = (C.c_void_p * max(K, 1))(*[r.ctypes.data for r in rows])
+    lib().orc_dasgd_apply_table(V, D, stride, dtype, _p(W), K, _p(n), idp, rwp, np.float32(lr))
+
+
+def dasgd_apply(W_in, W_out, D, dtype, grads, lr):
+    """Merged application of the own gradient grads[0] and peer gradients grads[1:]."""
+    dasgd_apply_table(W_in, D, dtype, [(g.gin.ids, g.gin.rows) for g in grads], lr)
+    dasgd_apply_table(W_out, D, dtype, [(g.gout.ids, g.gout.rows) for g in grads], lr)
+
+
+# ---------------------------------------------------------------- staleness
+def staleness(G_i, G_j) -> int:
+    """Section 3.1: |G_i u G_j| - |G_i n G_j| for the set G_i of gradients model i had
+    applied when it computed a gradient and the set G_j model j has applied when it
+    applies that gradient."""
+    G_i, G_j = set(G_i), set(G_j)
+    return len(G_i | G_j) - len(G_i & G_j)

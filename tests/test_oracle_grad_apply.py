@@ -1,0 +1,300 @@
+"""Pins for the oracle's gradient calculation and gradient application (CPU only).
+
+Each test checks the oracle against something other than itself: a closed form, a
+hand-worked example, finite differences, a tensor library's autograd, a dense
+brute-force accumulation, or an algebraic identity of Eq. 1."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+
+def _tiny(V=11, D=4, T=30, seed=0, dtype=oracle.F64, w_out_zero=False):
+    rng = np.random.default_rng(seed)
+    tok = rng.integers(0, V, size=T).astype(np.int32)
+    counts = np.bincount(tok, minlength=V).astype(np.uint64)
+    thr, alias = oracle.alias_build(counts)
+    npdt = {oracle.F64: np.float64, oracle.F32: np.float32}[dtype]
+    W_in = (rng.standard_normal((V, D)) * 0.5).astype(npdt)
+    W_out = np.zeros((V, D), npdt) if w_out_zero else (rng.standard_normal((V, D)) * 0.5).astype(npdt)
+    return tok, thr, alias, W_in, W_out
+
+
+def _dense(sr, V):
+    out = np.zeros((V, sr.rows64.shape[1]))
+    out[sr.ids] = sr.rows64
+    return out
+
+
+# ------------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("N", [1, 5, 10, 15])
+def test_loss_and_gradients_closed_form_when_w_out_is_zero(N):
+    """All logits are 0: loss = (N+1) ln 2, Gin = 0, Gout[j] = (1/P) sum_occ (1/2 - label) v_c."""
+    V, D, T, w = 13, 6, 40, 3
+    tok, thr, alias, W_in, W_out = _tiny(V, D, T, seed=N, w_out_zero=True)
+    g = oracle.sgns_grad(tok, w, N, 4, 9, D, oracle.F64, W_in, W_out, thr, alias, 11, 0, 0, want64=True)
+    assert g.loss == pytest.approx((N + 1) * math.log(2.0), rel=1e-14)
+    assert not g.gin.rows64.any()
+    assert g.gin.ids.tolist() == sorted(set(tok[4:13].tolist()))       # listed although zero
+    pos, q = oracle.pairs(T, w, 4, 9)
+    want = np.zeros((V, D))
+    for i, (p, qq) in enumerate(zip(pos, q)):
+        o = qq - w if qq < w else qq - w + 1
+        want[tok[p + o]] += (0.5 - 1.0) * W_in[tok[p]] / g.P
+        for k in range(N):
+            want[g.negatives[i, k]] += 0.5 * W_in[tok[p]] / g.P
+    assert np.allclose(_dense(g.gout, V), want, rtol=1e-13, atol=1e-16)
+
+
+def test_hand_worked_pair_d2():
+    """v = (ln 3, 0), u_pos = (1, 7), u_neg = (0, 0), one pair, one negative:
+    s_pos = ln 3, sigma = 3/4, g_pos = -1/4, g_neg = +1/2, loss = ln(4/3) + ln 2."""
+    tok = np.array([0, 1], dtype=np.int32)           # center at position 0, context = token 1
+    W_in = np.zeros((3, 2)); W_in[0] = (math.log(3.0), 0.0)
+    W_out = np.zeros((3, 2)); W_out[1] = (1.0, 7.0)
+    thr = np.full(3, 0xFFFFFFFF, np.uint32); alias = np.arange(3, dtype=np.int32)
+    g = oracle.sgns_grad(tok, 1, 1, 0, 1, 2, oracle.F64, W_in, W_out, thr, alias, 0, 0, 0,
+                         neg_override=np.array([[2]], np.int32), want64=True)
+    assert g.P == 1
+    assert g.loss == pytest.approx(math.log(4.0 / 3.0) + math.log(2.0), rel=1e-14)
+    assert g.gin.ids.tolist() == [0]
+    assert np.allclose(g.gin.rows64[0], [-0.25 * 1.0, -0.25 * 7.0], rtol=1e-14)
+    assert g.gout.ids.tolist() == [1, 2]
+    assert np.allclose(g.gout.rows64[0], [-0.25 * math.log(3.0), 0.0], rtol=1e-14)
+    assert np.allclose(g.gout.rows64[1], [0.5 * math.log(3.0), 0.0], rtol=1e-14)
+    assert g.gin.seg.tolist() == [0, 1] and g.gout.seg.tolist() == [0, 1, 2]
+
+
+# ------------------------------------------------------------------ finite differences
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_gradient_by_central_finite_differences(seed):
+    V, D, T, w, N = 11, 4, 30, 2, 3
+    tok, thr, alias, W_in, W_out = _tiny(V, D, T, seed)
+    begin, n = 5, 3
+    base = oracle.sgns_grad(tok, w, N, begin, n, D, oracle.F64, W_in, W_out, thr, alias, 5, 0, 0, want64=True)
+    neg = base.negatives.copy()
+    # make sure the degenerate coincidences are exercised: a negative equal to its center and to its context
+    pos, q = oracle.pairs(T, w, begin, n)
+    o0 = q[0] - w if q[0] < w else q[0] - w + 1
+    neg[0, 0] = tok[pos[0]]
+    neg[0, 1] = tok[pos[0] + o0]
+    base = oracle.sgns_grad(tok, w, N, begin, n, D, oracle.F64, W_in, W_out, thr, alias, 5, 0, 0,
+                            neg_override=neg, want64=True)
+    Gin, Gout = _dense(base.gin, V), _dense(base.gout, V)
+
+    def loss(A, B):
+        return oracle.sgns_grad(tok, w, N, begin, n, D, oracle.F64, A, B, thr, alias, 5, 0, 0,
+                                neg_override=neg).loss
+
+    h = 1e-5
+    for (W, G, which) in ((W_in, Gin, 0), (W_out, Gout, 1)):
+        fd = np.zeros_like(G)
+        for r in range(V):
+            for d in range(D):
+                Wp, Wm = W.copy(), W.copy()
+                Wp[r, d] += h
+                Wm[r, d] -= h
+                fd[r, d] = ((loss(Wp, W_out) - loss(Wm, W_out)) if which == 0
+                            else (loss(W_in, Wp) - loss(W_in, Wm))) / (2 * h)
+        assert np.allclose(fd, G, rtol=1e-7, atol=1e-9), which
+        # rows the sparse form does not list have zero derivative
+        listed = set((base.gin if which == 0 else base.gout).ids.tolist())
+        for r in range(V):
+            if r not in listed:
+                assert not fd[r].any()
+
+
+# ------------------------------------------------------------------ library autograd
+def test_gradient_matches_autograd_of_the_sgns_loss():
+    V, D, T, w, N = 40, 8, 120, 3, 5
+    tok, thr, alias, W_in, W_out = _tiny(V, D, T, seed=7)
+    begin, n = 10, 32
+    g = oracle.sgns_grad(tok, w, N, begin, n, D, oracle.F64, W_in, W_out, thr, alias, 21, 2, 1, want64=True)
+    pos, q = oracle.pairs(T, w, begin, n)
+    off = np.where(q < w, q - w, q - w + 1)
+    c = torch.from_numpy(tok[pos].astype(np.int64))
+    x = torch.from_numpy(tok[pos + off].astype(np.int64))
+    ng = torch.from_numpy(g.negatives.astype(np.int64))
+    A = torch.tensor(W_in, requires_grad=True)
+    B = torch.tensor(W_out, requires_grad=True)
+    v = A[c]
+    s_pos = (v * B[x]).sum(-1)
+    s_neg = torch.einsum("pd,pnd->pn", v, B[ng])
+    L = (torch.nn.functional.softplus(-s_pos) + torch.nn.functional.softplus(s_neg).sum(-1)).mean()
+    L.backward()
+    assert g.loss == pytest.approx(float(L.detach()), rel=1e-12)
+    assert np.allclose(_dense(g.gin, V), A.grad.numpy(), rtol=1e-10, atol=1e-14)
+    assert np.allclose(_dense(g.gout, V), B.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+# ------------------------------------------------------------------ duplicates / sparse form
+@pytest.mark.parametrize("hot", [False, True])
+def test_sparse_form_against_dense_brute_force(hot):
+    V, D, T, w, N = 9, 3, 50, 4, 6
+    tok, thr, alias, W_in, W_out = _tiny(V, D, T, seed=3)
+    if hot:
+        tok[:] = 4                                   # every center and context is the same row
+        thr, alias = oracle.alias_build(np.bincount(tok, minlength=V).astype(np.uint64))
+    g = oracle.sgns_grad(tok, w, N, 0, T, D, oracle.F64, W_in, W_out, thr, alias, 8, 0, 0, want64=True)
+    pos, q = oracle.pairs(T, w, 0, T)
+    Gin, Gout = np.zeros((V, D)), np.zeros((V, D))
+    occ_in, occ_out = np.zeros(V, np.int64), np.zeros(V, np.int64)
+    for i, (p, qq) in enumerate(zip(pos, q)):
+        o = qq - w if qq < w else qq - w + 1
+        c = tok[p]
+        occ_in[c] += 1
+        for k, j in enumerate([tok[p + o]] + g.negatives[i].tolist()):
+            s = float(W_in[c] @ W_out[j])
+            gg = (1.0 / (1.0 + math.exp(-s)) - (1.0 if k == 0 else 0.0)) / len(pos)
+            Gin[c] += gg * W_out[j]
+            Gout[j] += gg * W_in[c]
+            occ_out[j] += 1
+    for sr, G, occ in ((g.gin, Gin, occ_in), (g.gout, Gout, occ_out)):
+        assert sr.ids.tolist() == np.nonzero(occ)[0].tolist()            # ascending unique = nonzero bins
+        assert sr.seg.tolist() == np.concatenate([[0], np.cumsum(occ[occ > 0])]).tolist()
+        assert np.allclose(_dense(sr, V), G, rtol=1e-12, atol=1e-15)
+    assert g.gout.seg[-1] == len(pos) * (N + 1) and g.gin.seg[-1] == len(pos)
+    if hot:
+        assert g.gin.ids.tolist() == [4]
+    # float export is the rounded double accumulator
+    assert np.array_equal(g.gout.rows, g.gout.rows64.astype(np.float32))
+
+
+def test_empty_batch():
+    tok, thr, alias, W_in, W_out = _tiny()
+    g = oracle.sgns_grad(tok, 2, 3, 5, 0, 4, oracle.F64, W_in, W_out, thr, alias, 1, 0, 0)
+    assert g.P == 0 and g.gin.ids.size == 0 and g.gout.ids.size == 0 and g.loss == 0.0
+    # a single-token stream has a center but no context
+    g = oracle.sgns_grad(np.array([3], np.int32), 2, 3, 0, 1, 4, oracle.F64, W_in, W_out, thr, alias, 1, 0, 0)
+    assert g.P == 0
+
+
+# ------------------------------------------------------------------ apply (Eq. 1)
+def _rand_sparse(rng, V, D, U):
+    ids = np.sort(rng.choice(V, size=U, replace=False)).astype(np.int32)
+    return ids, rng.standard_normal((U, D)).astype(np.float32)
+
+
+def test_apply_is_eq1_for_a_single_gradient():
+    rng = np.random.default_rng(0)
+    V, D = 50, 6
+    W = rng.standard_normal((V, D)).astype(np.float32)
+    W0 = W.copy()
+    ids, rows = _rand_sparse(rng, V, D, 17)
+    lr = 0.025
+    oracle.dasgd_apply_table(W, D, oracle.F32, [(ids, rows)], lr)
+    want = W0.copy()
+    want[ids] = (W0[ids].astype(np.float64) - float(np.float32(lr)) * rows.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(W, want)
+    untouched = np.setdiff1d(np.arange(V), ids)
+    assert np.array_equal(W[untouched].view(np.uint32), W0[untouched].view(np.uint32))
+
+
+def test_apply_respects_row_stride_padding():
+    rng = np.random.default_rng(1)
+    V, D, S = 20, 5, 8
+    W = rng.standard_normal((V, S)).astype(np.float32)
+    W0 = W.copy()
+    ids, rows = _rand_sparse(rng, V, D, 9)
+    oracle.dasgd_apply_table(W, D, oracle.F32, [(ids, rows)], 0.5)
+    assert np.array_equal(W[:, D:], W0[:, D:])
+    assert not np.array_equal(W[ids, :D], W0[ids, :D])
+
+
+def test_merged_apply_equals_sequential_applies_and_ignores_peer_order():
+    rng = np.random.default_rng(2)
+    V, D, K = 80, 7, 5
+    W0 = rng.standard_normal((V, D))
+    srcs = [_rand_sparse(rng, V, D, int(rng.integers(1, 40))) for _ in range(K + 1)]
+    merged = W0.copy()
+    oracle.dasgd_apply_table(merged, D, oracle.F64, srcs, 0.025)
+    seq = W0.copy()
+    for s in srcs:                                       # Algorithm 1: one apply_gradient per message
+        oracle.dasgd_apply_table(seq, D, oracle.F64, [s], 0.025)
+    assert np.allclose(merged, seq, rtol=1e-14, atol=1e-15)
+    perm = W0.copy()
+    oracle.dasgd_apply_table(perm, D, oracle.F64, [srcs[0]] + srcs[:0:-1], 0.025)
+    assert np.allclose(merged, perm, rtol=1e-15, atol=1e-16)
+    # summed, not averaged: two copies of one gradient move the row twice as far
+    a, b = W0.copy(), W0.copy()
+    oracle.dasgd_apply_table(a, D, oracle.F64, [srcs[0]], 0.025)
+    oracle.dasgd_apply_table(b, D, oracle.F64, [srcs[0], srcs[0]], 0.025)
+    i = srcs[0][0]
+    assert np.allclose(b[i] - W0[i], 2 * (a[i] - W0[i]), rtol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_apply_then_unapply_restores_within_rounding(dtype):
+    rng = np.random.default_rng(4)
+    V, D = 60, 8
+    Wf = (rng.standard_normal((V, D)) * 0.1).astype(np.float32)
+    if dtype == oracle.BF16:
+        W = torch.from_numpy(Wf).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+    else:
+        W = Wf.copy()
+    W0 = W.copy()
+    ids, rows = _rand_sparse(rng, V, D, 25)
+    oracle.dasgd_apply_table(W, D, dtype, [(ids, rows)], 0.025)
+    assert not np.array_equal(W, W0)
+    W1 = W.copy()
+    oracle.dasgd_apply_table(W, D, dtype, [(ids, -rows)], 0.025)
+
+    def val(a):
+        return (a.astype(np.float64) if dtype == oracle.F32 else oracle.bf16_to_f32(a).astype(np.float64))
+
+    def ulp(a):
+        bits = 23 if dtype == oracle.F32 else 7
+        return 2.0 ** (np.floor(np.log2(np.maximum(np.abs(val(a)), 1e-30))) - bits)
+
+    # two roundings, each at most half a unit in the last place of the value it produced:
+    # floating-point subtraction is not invertible, so "restores" can only mean this bound
+    assert np.all(np.abs(val(W) - val(W0)) <= 0.5 * (ulp(W1) + ulp(W)) * (1 + 1e-12))
+    # exact when every intermediate is representable: table on a 2^-4 grid, update 2^-3
+    Wg = (rng.integers(-32, 33, size=(V, D)) / 16.0).astype(np.float32)
+    W = (torch.from_numpy(Wg).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+         if dtype == oracle.BF16 else Wg.copy())
+    W0 = W.copy()
+    rows2 = np.full_like(rows, 0.5)
+    oracle.dasgd_apply_table(W, D, dtype, [(ids, rows2)], 0.25)
+    assert np.array_equal(val(W)[ids], val(W0)[ids] - 0.125)
+    oracle.dasgd_apply_table(W, D, dtype, [(ids, -rows2)], 0.25)
+    assert np.array_equal(W, W0)
+
+
+def test_bf16_apply_rounds_once_from_the_exact_sum():
+    """Three gradients whose individual updates are each below half a bf16 ulp move the row
+    when summed first (fp32-accumulated, rounded once) -- K+1 separate roundings would not."""
+    W = np.array([[0x3F80]], dtype=np.uint16)                    # 1.0; ulp above = 2^-7
+    g = np.array([[-(2.0 ** -9) * 1.1]], dtype=np.float32)       # update +0.275 ulp each at lr = 1
+    ids = np.array([0], np.int32)
+    one = W.copy()
+    oracle.dasgd_apply_table(one, 1, oracle.BF16, [(ids, g)], 1.0)
+    assert one[0, 0] == 0x3F80
+    three = W.copy()
+    oracle.dasgd_apply_table(three, 1, oracle.BF16, [(ids, g)] * 3, 1.0)
+    assert three[0, 0] == 0x3F81
+
+
+def test_single_worker_step_is_minibatch_sgd():
+    """With one rank the update is plain synchronous SGD (Section 4.1): one oracle step equals
+    theta - alpha * autograd gradient of the batch-mean loss."""
+    V, D, T, w, N = 30, 5, 80, 2, 4
+    tok, thr, alias, W_in, W_out = _tiny(V, D, T, seed=9)
+    g = oracle.sgns_grad(tok, w, N, 0, 16, D, oracle.F64, W_in, W_out, thr, alias, 3, 0, 0)
+    A, B = W_in.copy(), W_out.copy()
+    oracle.dasgd_apply(A, B, D, oracle.F64, [g], 0.025)
+    pos, q = oracle.pairs(T, w, 0, 16)
+    off = np.where(q < w, q - w, q - w + 1)
+    tA = torch.tensor(W_in, requires_grad=True)
+    tB = torch.tensor(W_out, requires_grad=True)
+    v = tA[torch.from_numpy(tok[pos].astype(np.int64))]
+    sp = (v * tB[torch.from_numpy(tok[pos + off].astype(np.int64))]).sum(-1)
+    sn = torch.einsum("pd,pnd->pn", v, tB[torch.from_numpy(g.negatives.astype(np.int64))])
+    (torch.nn.functional.softplus(-sp) + torch.nn.functional.softplus(sn).sum(-1)).mean().backward()
+    lr = float(np.float32(0.025))
+    # the sparse gradient crosses the interface as float32, hence the 1e-7 relative slack
+    assert np.allclose(A, W_in - lr * tA.grad.numpy(), rtol=0, atol=2e-8)
+    assert np.allclose(B, W_out - lr * tB.grad.numpy(), rtol=0, atol=2e-8)
