@@ -1,0 +1,166 @@
+/*
+ * libtensair -- one DASGD worker's training step on a skip-gram/negative-sampling
+ * word-embedding model, for AMD MI355X (gfx950).
+ *
+ * The calls follow the Model operator of TensAIR (arXiv 2211.10280), Algorithm 1:
+ *   Model(tfModel, maxBuffer)            -> tensair_model_init
+ *   calculate_gradient(model, minibatch) -> tensair_sgns_grad      (gradient calculation, Section 2.2)
+ *   apply_gradient(model, gradient)      -> tensair_dasgd_apply    (gradient application, Eq. 1)
+ *   train(minibatch) incl. peer messages -> tensair_step
+ *
+ * Conventions for every call
+ *   - Plain C ABI.  Pointers marked DEVICE point to GPU memory owned by the caller;
+ *     pointers marked HOST point to host memory.  The library allocates no device
+ *     memory: everything it needs lives in the caller's workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All GPU
+ *     work is enqueued on it; no call waits for the GPU except tensair_status and
+ *     tensair_model_init (which uploads the alias table).  Sizes that depend on the data
+ *     (number of unique rows) stay on the device.
+ *   - Return value: TENSAIR_OK or a negative tensair_status code; host-detectable
+ *     argument errors are reported before anything is launched;
+ *     tensair_last_error() gives a thread-local message.
+ *   - Data errors seen by kernels (a peer gradient whose ids are out of range or not
+ *     strictly ascending) never fault: the offending rows are skipped, a device
+ *     status word is set, and tensair_status() reports TENSAIR_EDATA.
+ */
+#ifndef TENSAIR_H
+#define TENSAIR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tensair_model tensair_model; /* opaque host handle */
+
+enum { TENSAIR_F32 = 0, TENSAIR_BF16 = 1 }; /* table element type (gradients are always fp32) */
+
+enum {
+    TENSAIR_OK = 0,
+    TENSAIR_EINVAL = -1,    /* bad argument (null, non-positive size, unsupported shape) */
+    TENSAIR_ECAPACITY = -2, /* a caller buffer or the workspace is too small */
+    TENSAIR_EHIP = -3,      /* a HIP runtime call failed */
+    TENSAIR_EDATA = -4      /* kernels met invalid row ids */
+};
+
+#define TENSAIR_MAX_DIM 1024  /* dim must be a multiple of 4, 4..1024 */
+#define TENSAIR_MAX_PEERS 31
+
+typedef struct {
+    int64_t vocab;       /* V, 1 .. 2^31-1 */
+    int32_t dim;         /* D, multiple of 4 */
+    int32_t row_stride;  /* elements between consecutive table rows, >= dim, multiple of 4 */
+    int32_t dtype;       /* TENSAIR_F32 | TENSAIR_BF16 */
+    int32_t window;      /* w >= 1: contexts at offsets -w..-1, +1..+w, clipped to the stream */
+    int32_t negatives;   /* N >= 0 negatives per (center, context) pair */
+    int32_t max_centers; /* largest mini-batch (center positions) a call may pass */
+    int32_t max_peers;   /* largest number of peer gradients a call may pass, <= TENSAIR_MAX_PEERS */
+    uint32_t worker_id;  /* < 65536; enters the negative-sampling counter (peers differ by it) */
+    uint64_t seed;       /* key of the counter-based generator (negatives and table init) */
+} tensair_config;
+
+/* One table's sparse gradient: the rows a mini-batch touches (Section 4, "Sparse vs.
+ * Dense Models").  All pointers DEVICE, caller-owned.  row_ids[0..*n_rows) is strictly
+ * ascending; row_grads is [capacity][dim] fp32, dense rows, no padding. */
+typedef struct {
+    int64_t capacity;  /* rows allocated in row_ids / row_grads */
+    int32_t *n_rows;   /* device scalar: written by tensair_sgns_grad, read by tensair_dasgd_apply */
+    int32_t *row_ids;
+    float *row_grads;
+} tensair_sparse_rows;
+
+/* Gradient of one mini-batch: `in` = rows of W_in (centers), `out` = rows of W_out
+ * (contexts and negatives).  This is the payload of a gradient message of Algorithm 1. */
+typedef struct {
+    tensair_sparse_rows in, out;
+} tensair_sparse_grad;
+
+/* Bytes of DEVICE workspace tensair_model_init needs for `cfg` (0 if cfg is invalid). */
+size_t tensair_workspace_bytes(const tensair_config *cfg);
+
+/* Rows a tensair_sparse_grad must hold for a batch of `n_centers`:
+ * in: min(V, n_centers); out: min(V, 2*w*n_centers*(N+1)). */
+int64_t tensair_capacity_in(const tensair_config *cfg, int32_t n_centers);
+int64_t tensair_capacity_out(const tensair_config *cfg, int32_t n_centers);
+
+/* Constructor of Algorithm 1's Model: binds the two embedding tables
+ * (DEVICE, [vocab][row_stride] of cfg->dtype, 16-byte aligned, caller-owned).
+ * fill_tables = 1: a fresh model, W_in ~ U(-0.5/D, 0.5/D) from cfg->seed, W_out = 0
+ * (padding columns zeroed); 0: adopt the contents (a pre-trained model).
+ * unigram_counts: HOST [vocab] occurrence counts; the noise distribution is
+ * count^0.75 / sum, stored as an alias table in the workspace.
+ * workspace: DEVICE, 256-byte aligned, >= tensair_workspace_bytes(cfg), and kept alive
+ * and untouched by the caller until tensair_model_destroy.
+ * Waits for the upload of the alias table on `stream` before returning. */
+int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_in, void *w_out,
+                       int fill_tables, const uint64_t *unigram_counts, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/* Point the model at other tables of the same shape and type (e.g. an older snapshot,
+ * which is how a stale peer of Section 3.1 is reproduced) and change the worker id. */
+int tensair_model_rebind(tensair_model *m, void *w_in, void *w_out, uint32_t worker_id);
+
+/* Copy the alias table to HOST arrays thr[vocab], alias[vocab].  A draw (b, r) with
+ * bucket b and 32-bit uniform r yields b if r < thr[b], else alias[b]. */
+int tensair_model_alias(const tensair_model *m, uint32_t *thr, int32_t *alias);
+
+/* Number of (center, context) pairs of the mini-batch of center positions
+ * [center_begin, center_begin + n_centers) in a stream of n_tokens (host arithmetic). */
+int64_t tensair_pair_count(const tensair_model *m, int64_t n_tokens, int64_t center_begin,
+                           int32_t n_centers);
+
+/* calculate_gradient of Algorithm 1 for one mini-batch, on the tables as they stand.
+ * tokens: DEVICE int32[n_tokens], ids in [0, vocab).  The mini-batch is the run of
+ * center positions [center_begin, center_begin+n_centers), n_centers <= max_centers.
+ * Pairs are enumerated center-ascending, offsets -w..-1,+1..+w; each pair draws N
+ * negatives from Philox4x32-10(counter = (position lo, position hi, q*65536+slot,
+ * worker_id + 65536*epoch), key = seed): word 0 picks the bucket by multiply-high,
+ * word 1 is compared with the bucket's threshold.  Per pair and j in {context,
+ * negatives}: s = <W_in[c], W_out[j]>, g = (sigmoid(s) - label)/P; Gin[c] += g W_out[j],
+ * Gout[j] += g W_in[c] (fp32 accumulation in a fixed order, duplicates summed by
+ * sort and segmented reduction, no atomics).
+ * grad_out: capacities >= tensair_capacity_in/out(n_centers); receives n_rows, the
+ * ascending unique row ids and the summed rows.
+ * Optional DEVICE outputs (NULL to skip): mean_loss float[1] (mean over the P pairs);
+ * negatives_dbg int32[P][N]; seg_offsets_in int32[U_in+1] / seg_offsets_out
+ * int32[U_out+1] = number of occurrences with a smaller id (in: one per pair; out: N+1
+ * per pair: context, then negatives), last entry = total. */
+int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
+                      int64_t center_begin, int32_t n_centers, uint32_t epoch,
+                      tensair_sparse_grad *grad_out, float *mean_loss, int32_t *negatives_dbg,
+                      int32_t *seg_offsets_in, int32_t *seg_offsets_out, void *stream);
+
+/* apply_gradient of Algorithm 1 / Eq. 1 for the own gradient and n_peers received
+ * gradients at once: for every row r in the union of their row ids,
+ * W[r] <- W[r] - lr * (own[r] + peer_1[r] + ... + peer_K[r]), the sum taken in fp32 in
+ * that order, one rounding on store (round-to-nearest-even for bf16 tables).  Rows
+ * outside the union are not written.  own may be NULL (peers only).  peers: HOST array
+ * of n_peers structs (device pointers inside), n_peers <= max_peers.  Each source's ids
+ * must be strictly ascending and in range (else TENSAIR_EDATA via tensair_status). */
+int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own,
+                        const tensair_sparse_grad *peers, int32_t n_peers, float lr, void *stream);
+
+/* train() of Algorithm 1 for one mini-batch plus the peer gradients that arrived:
+ * tensair_sgns_grad into own_out on the current tables, then tensair_dasgd_apply of
+ * own_out and the peers (Section 3.1: the own gradient is computed before the
+ * received ones are applied).  own_out stays valid afterwards (it is what the worker
+ * would broadcast). */
+int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                 int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers,
+                 int32_t n_peers, float lr, tensair_sparse_grad *own_out, float *mean_loss,
+                 void *stream);
+
+/* Waits for `stream`, then returns TENSAIR_OK, TENSAIR_EDATA (and clears the device
+ * status word) or TENSAIR_EHIP. */
+int tensair_status(tensair_model *m, void *stream);
+
+int tensair_model_destroy(tensair_model *m);
+
+const char *tensair_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENSAIR_H */

@@ -1,0 +1,183 @@
+// Device-side helpers shared by the kernels of libtensair (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int64_t i64;
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+#define WAVE 64
+#define BLOCK 256
+#define WAVES_PER_BLOCK (BLOCK / WAVE)
+
+// status word bits (device), reported as TENSAIR_EDATA
+#define ST_BAD_ID 1
+#define ST_BAD_ORDER 2
+#define ST_OVERFLOW 4
+
+// ---------------------------------------------------------------- bf16
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((u32)h << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    u32 u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------- 4-element chunks of a row
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 ld4(const bf16_t *p)
+{
+    uint2 r = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ void st4(bf16_t *p, float4 v)
+{
+    uint2 r;
+    r.x = (u32)f32_to_bf16(v.x) | ((u32)f32_to_bf16(v.y) << 16);
+    r.y = (u32)f32_to_bf16(v.z) | ((u32)f32_to_bf16(v.w) << 16);
+    *reinterpret_cast<uint2 *>(p) = r;
+}
+
+// A row of D = 4*C4 elements is held by one wave: lane l owns chunks l, l+64, ...
+// (ITERS = ceil(C4/64) chunks per lane, compile-time).
+template <typename T, int ITERS>
+__device__ __forceinline__ void load_row(float4 (&r)[ITERS], const T *row, int C4, int lane)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        r[it] = (c < C4) ? ld4(row + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+template <typename T, int ITERS>
+__device__ __forceinline__ void store_row(T *row, const float4 (&r)[ITERS], int C4, int lane)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        if (c < C4) st4(row + 4 * c, r[it]);
+    }
+}
+template <int ITERS>
+__device__ __forceinline__ void zero_row(float4 (&r)[ITERS])
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) r[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+template <int ITERS>
+__device__ __forceinline__ void axpy_row(float4 (&acc)[ITERS], float a, const float4 (&x)[ITERS])
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        acc[it].x = fmaf(a, x[it].x, acc[it].x);
+        acc[it].y = fmaf(a, x[it].y, acc[it].y);
+        acc[it].z = fmaf(a, x[it].z, acc[it].z);
+        acc[it].w = fmaf(a, x[it].w, acc[it].w);
+    }
+}
+template <int ITERS>
+__device__ __forceinline__ void add_row(float4 (&acc)[ITERS], const float4 (&x)[ITERS])
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        acc[it].x += x[it].x;
+        acc[it].y += x[it].y;
+        acc[it].z += x[it].z;
+        acc[it].w += x[it].w;
+    }
+}
+template <int ITERS>
+__device__ __forceinline__ float dot_partial(const float4 (&a)[ITERS], const float4 (&b)[ITERS])
+{
+    float s = 0.f;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        s = fmaf(a[it].x, b[it].x, s);
+        s = fmaf(a[it].y, b[it].y, s);
+        s = fmaf(a[it].z, b[it].z, s);
+        s = fmaf(a[it].w, b[it].w, s);
+    }
+    return s;
+}
+
+// ---------------------------------------------------------------- wave-level primitives
+// butterfly sum: every lane ends with the same value, the order of additions is fixed
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
+    return x;
+}
+__device__ __forceinline__ u32 wave_or(u32 x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x |= (u32)__shfl_xor((int)x, o, WAVE);
+    return x;
+}
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+__device__ __forceinline__ int rd_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ float rd_lane(float v, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ u64 rd_lane64(u64 v, int l)
+{
+    u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, l);
+    u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), l);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// inclusive scan of one value per lane across the wave
+__device__ __forceinline__ u32 wave_incl_scan(u32 x, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        u32 y = (u32)__shfl_up((int)x, o, WAVE);
+        if (lane >= o) x += y;
+    }
+    return x;
+}
+
+// ---------------------------------------------------------------- Philox4x32-10
+// Counter-based generator of Salmon et al. (SC'11): 10 rounds, multipliers
+// 0xD2511F53 / 0xCD9E8D57, key increments 0x9E3779B9 / 0xBB67AE85.
+struct philox_out {
+    u32 r0, r1, r2, r3;
+};
+__device__ __forceinline__ philox_out philox4x32_10(u32 c0, u32 c1, u32 c2, u32 c3, u32 k0, u32 k1)
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        u32 hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        u32 hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        u32 n0 = hi1 ^ c1 ^ k0;
+        u32 n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return philox_out{c0, c1, c2, c3};
+}
+
+// ---------------------------------------------------------------- pair arithmetic
+// Number of (center, context) pairs of the positions [0, p) in a stream of T tokens with
+// window w: position x has min(x, w) contexts on the left and min(T-1-x, w) on the right.
+__host__ __device__ __forceinline__ i64 sum_min_below(i64 x, i64 w)
+{   // sum_{y=0}^{x-1} min(y, w)
+    if (x <= 0) return 0;
+    if (x <= w + 1) return x * (x - 1) / 2;
+    return w * (w + 1) / 2 + (x - w - 1) * w;
+}
+__host__ __device__ __forceinline__ i64 pairs_before(i64 p, i64 T, i64 w)
+{
+    return sum_min_below(p, w) + sum_min_below(T, w) - sum_min_below(T - p, w);
+}

@@ -1,0 +1,121 @@
+// Host-callable launchers of the HIP kernels (one per pipeline stage).  All of them only
+// enqueue work on `st`; none synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int64_t i64;
+
+#define TN_MAX_SRC 32     // own + up to 31 peers
+#define TN_SEG_TILE 64    // sorted entries per wave in the segmented reduction
+#define TN_RADIX_TILE 2048  // keys per block in a radix pass (256 threads x 8)
+#define TN_SCAN_TILE 2048   // entries per block in the head scan
+
+// ---- stage 0: table initialisation
+void tn_launch_init_tables(void *w_in, void *w_out, i64 V, int D, int stride, int dtype, u64 seed,
+                           hipStream_t st);
+
+// ---- stage 1: pair enumeration, negative sampling, sort keys
+struct BatchDesc {
+    const int *tok;   // DEVICE int32[T]
+    i64 T;
+    i64 begin;        // first center position
+    int n_centers;
+    int w, N;
+    i64 pair_base;    // pairs_before(begin)
+    i64 P;            // pairs in the batch
+};
+void tn_launch_build_keys(const BatchDesc &b, i64 V, const u32 *thr, const int *alias, u64 seed,
+                          u32 worker, u32 epoch, u32 *out_keys, u32 *in_keys, int *pair_center,
+                          int *neg_dbg, int *status, hipStream_t st);
+
+// ---- stage 2: stable LSD radix sort of (key, value) for two independent problems at once
+struct RadixProb {
+    u32 *keys[2];   // ping-pong buffers; input in keys[0]
+    u32 *vals[2];   // values; the first pass writes the entry index (input order) itself
+    int n;
+    int nblk;       // ceil(n / TN_RADIX_TILE)
+    u32 *counts;    // [2^bits][nblk] scratch
+    u32 *totals;    // [2^bits] scratch
+};
+// returns which buffer (0/1) holds the sorted result
+int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st);
+
+// ---- stage 3: unique ids, segment index of every sorted entry, weighted segment offsets
+struct SegProb {
+    const u32 *keys;      // sorted keys
+    const u32 *vals;      // sorted values
+    int n;
+    int nblk;             // ceil(n / TN_SCAN_TILE)
+    int *blk_heads;       // [nblk] scratch
+    int *blk_weight;      // [nblk] scratch
+    int *seg_of;          // [n] out: row index (0..U-1) of every sorted entry
+    int *row_ids;         // [capacity] out
+    int *n_rows;          // [1] out
+    int *seg_offsets;     // [U+1] out or NULL
+    i64 capacity;
+    int weighted;         // 0: every entry weighs 1; 1: entry = center index, weighs its pair count
+};
+void tn_launch_segments(SegProb p0, SegProb p1, i64 begin, i64 T, int w, int *status, hipStream_t st);
+
+// ---- stage 4: forward pass and per-center partial of the W_in gradient
+struct FwdArgs {
+    const void *w_in, *w_out;
+    i64 V;
+    int dtype, D, stride;
+    BatchDesc b;
+    const u32 *out_keys;   // unsorted out-side keys [P][N+1]
+    float *g;              // [P][N+1] out: (sigmoid - label)/P per occurrence
+    float *center_part;    // [n_centers][D] out
+    float *center_loss;    // [n_centers] out (sum of the loss terms, not yet divided by P)
+    float inv_P;
+};
+void tn_launch_forward(const FwdArgs &a, hipStream_t st);
+
+// ---- stage 5: segmented reduction of rows (duplicates summed in sorted order)
+struct SegReduceArgs {
+    int n;                 // sorted entries
+    const u32 *vals;       // sorted values
+    const int *seg_of;     // row index per sorted entry
+    float *out_rows;       // [U][D]
+    float *part;           // [ntiles][2][D] scratch for rows that cross tile borders
+    int D;
+    // source of the contribution of an entry:
+    //  mode 0 (out-side): value = occurrence index o; row = g[o] * W_in[pair_center[o/(N+1)]]
+    //  mode 1 (in-side):  value = center index i;     row = center_part[i]
+    int mode;
+    const float *g;
+    const int *pair_center;
+    int Np1;
+    const void *table;
+    int dtype, stride;
+    const float *center_part;
+};
+void tn_launch_segreduce(const SegReduceArgs &a, hipStream_t st);
+
+void tn_launch_loss(const float *center_loss, int n_centers, float inv_P, float *mean_loss,
+                    hipStream_t st);
+void tn_launch_empty_grad(int *n_in, int *n_out, float *mean_loss, int *seg_in, int *seg_out,
+                          hipStream_t st);
+
+// ---- stage 6/7: DASGD merge and table update
+struct ApplySrc {
+    const int *ids;
+    const float *rows;
+    const int *n_rows;
+    i64 capacity;
+};
+struct ApplyArgs {
+    void *table[2];          // W_in, W_out
+    int dtype, D, stride;
+    i64 V;
+    int n_src;               // own + peers actually passed
+    ApplySrc src[2][TN_MAX_SRC];
+    u32 *start[2];           // [words+1][n_src]
+    u64 *mask[2];            // [words][n_src]
+    float lr;
+    int *status;
+};
+void tn_launch_apply(const ApplyArgs &a, hipStream_t st);

@@ -1,0 +1,86 @@
+"""One DASGD worker among K+1 Model instances, on one GPU.
+
+Drives ``tensair_step`` over a synthetic workload the way the paper's dataflow
+would (TensAIR, arXiv 2211.10280, Algorithm 1 and Section 3.1): this worker
+receives every (K+1)-th mini-batch; before each of its steps the K gradients of
+the other instances "arrive".  With one GPU there are no other instances, so
+their gradients are produced here with ``tensair_sgns_grad`` on the peers' own
+mini-batches against a snapshot of this worker's model that is 0..max_stale
+steps old (the staleness of Section 3.1, counted in this worker's steps).
+Everything numerical happens inside the library; this file only sequences calls
+and keeps buffers.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workload as W
+
+
+class DasgdWorker:
+    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda"):
+        self.cfg = cfg
+        self.device = device
+        dt = B.F32 if cfg.dtype == "f32" else B.BF16
+        self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
+        self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
+                             max(cfg.peers, 0), cfg.seed, counts, worker_id=0, device=device)
+        # a second handle computes the peers' gradients on snapshots (its tables are rebound per call)
+        self.peer_model = None
+        if cfg.peers > 0:
+            self.peer_model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch, 0,
+                                      cfg.seed, counts, worker_id=1,
+                                      tables=(self.model.w_in, self.model.w_out), device=device)
+        self.own = self.model.grad_buffers()
+        self.peer_bufs = [self.model.grad_buffers() for _ in range(cfg.peers)]
+        self.snapshots = {}          # step -> (w_in, w_out) clones of theta_step
+        self.mean_loss = torch.zeros(1, dtype=torch.float32, device=device)
+        self.step_no = 0
+        self.stale = None
+
+    # -- peers -------------------------------------------------------------
+    def _snapshot(self, t):
+        if self.cfg.peers == 0:
+            return
+        if self.cfg.max_stale == 0:
+            self.snapshots = {t: (self.model.w_in, self.model.w_out)}   # only theta_t itself is used
+            return
+        self.snapshots[t] = (self.model.w_in.clone(), self.model.w_out.clone())
+        for old in [s for s in self.snapshots if s < t - self.cfg.max_stale]:
+            del self.snapshots[old]
+
+    def make_peer_grads(self, t, n_steps_hint=4096):
+        """Gradients of peers 1..K for step t, each on theta_{max(0, t - staleness)}."""
+        cfg = self.cfg
+        if self.stale is None or self.stale.shape[0] <= t:
+            self.stale = W.stale_draws(cfg, max(n_steps_hint, t + 1))
+        self._snapshot(t)
+        for k in range(1, cfg.peers + 1):
+            s = int(self.stale[t, k - 1])
+            w_in, w_out = self.snapshots[max(0, t - s)]
+            begin, n, epoch = W.worker_batch(cfg, t, k)
+            self.peer_model.rebind(w_in, w_out, k)
+            self.peer_model.sgns_grad(self.tokens, begin, n, epoch, self.peer_bufs[k - 1])
+        return self.peer_bufs
+
+    # -- one step -----------------------------------------------------------
+    def step(self, peers=None, want_loss=False):
+        """tensair_step for this worker's mini-batch of the current step."""
+        cfg = self.cfg
+        t = self.step_no
+        if peers is None:
+            peers = self.make_peer_grads(t) if cfg.peers else []
+        begin, n, epoch = W.worker_batch(cfg, t, 0)
+        self.model.step(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
+                        self.mean_loss if want_loss else None)
+        self.step_no += 1
+        return begin, n, epoch
+
+    def tables_to_host(self):
+        w_in, w_out = self.model.w_in, self.model.w_out
+        if self.cfg.dtype == "bf16":
+            return (w_in.view(torch.int16).cpu().numpy().view(np.uint16),
+                    w_out.view(torch.int16).cpu().numpy().view(np.uint16))
+        return w_in.cpu().numpy(), w_out.cpu().numpy()

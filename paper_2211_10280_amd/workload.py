@@ -46,11 +46,8 @@ class Config:
         return 1000 + self.idx
 
     @property
-    def init_seed(self) -> int:
-        return 2000 + self.idx
-
-    @property
-    def neg_seed(self) -> int:
+    def seed(self) -> int:
+        """Key of the model's counter-based generator (table init and negative draws)."""
         return 3000 + self.idx
 
     @property

@@ -1,0 +1,55 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-only calls
+behave (no GPU needed, no compute is launched)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2211_10280_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "tensair.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(tensair_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    if not os.path.exists(B.LIB_PATH):
+        pytest.fail("libtensair.so has not been built (python -m paper_2211_10280_amd.build)")
+    L = C.CDLL(B.LIB_PATH)
+    names = _declared()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.SYMBOLS) == names        # the binding forwards to exactly these
+
+
+def test_host_side_argument_checks():
+    L = B.lib()
+    good = B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7)
+    assert B.tensair_workspace_bytes(good) > 2 * 1000 * 4
+    assert B.tensair_capacity_in(good, 64) == 64
+    assert B.tensair_capacity_out(good, 64) == 1000          # min(V, 2*2*64*6 = 1536)
+    assert B.tensair_capacity_out(good, 10) == 240
+    for bad in (B.Config(0, 32, 32, B.F32, 2, 5, 64, 0, 0, 7),      # vocab
+                B.Config(1000, 30, 32, B.F32, 2, 5, 64, 0, 0, 7),    # dim not a multiple of 4
+                B.Config(1000, 32, 28, B.F32, 2, 5, 64, 0, 0, 7),    # stride < dim
+                B.Config(1000, 32, 32, 5, 2, 5, 64, 0, 0, 7),        # dtype
+                B.Config(1000, 32, 32, B.F32, 0, 5, 64, 0, 0, 7),    # window
+                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 32, 0, 7),   # too many peers
+                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 70000, 7)):  # worker id
+        with pytest.raises(B.TensairError):
+            B.tensair_workspace_bytes(bad)
+    assert L.tensair_last_error()                                # a message is left behind
+    # NULL handles are rejected, not dereferenced
+    assert L.tensair_model_rebind(None, None, None, 0) == B.EINVAL
+    assert L.tensair_dasgd_apply(None, None, None, 0, 0.1, None) == B.EINVAL
+    assert L.tensair_status(None, None) == B.EINVAL
+    assert L.tensair_pair_count(None, 10, 0, 1) == -1
+    h = C.c_void_p()
+    assert L.tensair_model_init(C.byref(h), C.byref(good), None, None, 1, None, None, 0, None) == B.EINVAL
+    assert h.value is None

@@ -1,0 +1,365 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Integer results (negatives, unique row ids, segment offsets, row counts, initial tables) must be
+bit-exact; fp32 gradient rows and tables within the tolerances of tests/helpers.py; bf16 tables
+within 2 ulp.  Inputs are seeded and synthetic (Zipf token streams)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import (BF16_ULP, TOL_DELTA, TOL_LOSS, TOL_ROWS, TOL_TABLE, bf16_to_f32, bf16_ulp_dist, rel_l2,
+                     rows_rel)
+from oracle.driver import OracleWorker
+from paper_2211_10280_amd import binding as B
+from paper_2211_10280_amd import workload as W
+from paper_2211_10280_amd.trainer import DasgdWorker
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f32": (B.F32, oracle.F32, torch.float32, np.float32),
+      "bf16": (B.BF16, oracle.BF16, torch.bfloat16, np.uint16)}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _tables_to_dev(w_np, dtype):
+    if dtype == "bf16":
+        return torch.from_numpy(w_np.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(w_np).cuda()
+
+
+def _tables_to_host(t, dtype):
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _random_tables(V, D, stride, dtype, seed, scale=0.3):
+    """'Pre-trained' tables as test data (both sides receive the same bits)."""
+    rng = np.random.default_rng(seed)
+    a = np.zeros((V, stride), np.float32)
+    b = np.zeros((V, stride), np.float32)
+    a[:, :D] = rng.standard_normal((V, D)).astype(np.float32) * scale
+    b[:, :D] = rng.standard_normal((V, D)).astype(np.float32) * scale
+    if dtype == "bf16":
+        conv = lambda x: torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+        return conv(a), conv(b)
+    return a, b
+
+
+# ------------------------------------------------------------------ init
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,D,stride", [(1000, 32, 32), (777, 300, 304), (64, 4, 8)])
+def test_init_tables_bit_exact(dtype, V, D, stride):
+    _say("init", dtype, V, D, stride)
+    bd, od, _, _ = DT[dtype]
+    counts = np.ones(V, np.uint64)
+    m = B.Model(V, D, bd, 2, 5, 64, 0, 0x1234567890ABCDEF, counts, row_stride=stride)
+    # poison the padding first: init must zero it
+    want_in, want_out = oracle.init_tables(V, D, stride, od, 0x1234567890ABCDEF)
+    got_in, got_out = _tables_to_host(m.w_in, dtype), _tables_to_host(m.w_out, dtype)
+    assert np.array_equal(got_in.view(np.uint8), want_in.view(np.uint8))
+    assert np.array_equal(got_out.view(np.uint8), want_out.view(np.uint8))
+    m.close()
+
+
+# ------------------------------------------------------------------ alias table
+@pytest.mark.parametrize("V,s", [(1000, 1.0), (50_000, 1.0), (300_000, 1.1)])
+def test_alias_table_equals_oracle(V, s):
+    _say("alias", V, s)
+    tok = W.zipf_stream(V, s, 400_000, 11)
+    counts = W.unigram_counts(tok, V)
+    m = B.Model(V, 32, B.F32, 2, 5, 64, 0, 1, counts)
+    thr, alias = m.alias()
+    othr, oalias = oracle.alias_build(counts)
+    assert np.array_equal(thr, othr) and np.array_equal(alias, oalias)
+    m.close()
+
+
+# ------------------------------------------------------------------ gradient calculation
+GRAD_CASES = [
+    # V,    D,   stride, T,     zipf, w, N,  B,    begin, dtype
+    (1000, 32, 32, 10_000, 1.0, 2, 5, 64, 0, "f32"),            # stream start: clipped windows
+    (1000, 32, 32, 10_000, 1.0, 2, 5, 16, 9_984, "f32"),        # last, partial batch at the stream end
+    (5000, 300, 300, 40_000, 1.1, 5, 10, 512, 1024, "f32"),     # D=300: ragged second chunk pass
+    (5000, 300, 320, 40_000, 1.1, 5, 10, 300, 777, "f32"),      # padded row stride
+    (5000, 128, 128, 40_000, 1.0, 5, 5, 1024, 2048, "bf16"),
+    (2000, 512, 512, 30_000, 1.05, 5, 10, 256, 4096, "bf16"),
+    (200, 256, 256, 20_000, 1.5, 8, 15, 1024, 512, "f32"),      # hot rows: segments span many tiles
+    (3, 64, 64, 5_000, 0.5, 3, 4, 700, 100, "f32"),             # three rows take everything
+    (100_000, 1024, 1024, 30_000, 1.0, 2, 3, 64, 5, "f32"),     # widest row (4 chunk passes), 17 key bits
+    (300, 4, 4, 2_000, 1.0, 1, 0, 128, 0, "f32"),               # narrowest row, no negatives
+    (5_000_000, 8, 8, 50_000, 0.8, 4, 6, 2048, 3000, "f32"),    # 23 key bits: three radix passes
+]
+
+
+@pytest.mark.parametrize("case", GRAD_CASES, ids=lambda c: f"V{c[0]}_D{c[1]}_B{c[7]}_{c[9]}")
+def test_sgns_grad_parity(case):
+    V, D, stride, T, zs, w, N, Bc, begin, dtype = case
+    _say("grad case", case)
+    bd, od, tdt, _ = DT[dtype]
+    tok = W.zipf_stream(V, zs, T, 5)
+    counts = W.unigram_counts(tok, V)
+    Wi, Wo = _random_tables(V, D, stride, dtype, seed=V + D)
+    d_in, d_out = _tables_to_dev(Wi, dtype), _tables_to_dev(Wo, dtype)
+    m = B.Model(V, D, bd, w, N, Bc, 0, 0xC0FFEE, counts, worker_id=3, row_stride=stride, tables=(d_in, d_out))
+    thr, alias = oracle.alias_build(counts)
+    og = oracle.sgns_grad(tok, w, N, begin, Bc, D, od, Wi, Wo, thr, alias, 0xC0FFEE, 3, 2)
+    P = og.P
+    assert m.pair_count(T, begin, Bc) == P
+
+    dtok = torch.from_numpy(tok).cuda()
+    g = m.grad_buffers(Bc)
+    loss = torch.zeros(1, device="cuda")
+    neg = torch.full((max(P * N, 1),), -1, dtype=torch.int32, device="cuda")
+    seg_in = torch.full((g.cap_in + 1,), -1, dtype=torch.int32, device="cuda")
+    seg_out = torch.full((g.cap_out + 1,), -1, dtype=torch.int32, device="cuda")
+    m.sgns_grad(dtok, begin, Bc, 2, g, mean_loss=loss, negatives_dbg=neg, seg_offsets_in=seg_in,
+                seg_offsets_out=seg_out)
+    m.status()
+    ui, uo = g.sizes()
+    (ids_in, rows_in), (ids_out, rows_out) = g.to_host()
+    # integers: bit-exact
+    assert np.array_equal(neg.cpu().numpy()[: P * N].reshape(P, N), og.negatives)
+    assert ui == og.gin.ids.size and uo == og.gout.ids.size
+    assert np.array_equal(ids_in, og.gin.ids) and np.array_equal(ids_out, og.gout.ids)
+    assert np.array_equal(seg_in.cpu().numpy()[: ui + 1], og.gin.seg.astype(np.int32))
+    assert np.array_equal(seg_out.cpu().numpy()[: uo + 1], og.gout.seg.astype(np.int32))
+    # floating point
+    e_in, e_out = rows_rel(rows_in, og.gin.rows), rows_rel(rows_out, og.gout.rows)
+    e_loss = abs(float(loss.item()) - og.loss) / og.loss
+    _say(f"   P={P} U_in={ui} U_out={uo} rows_rel in={e_in:.2e} out={e_out:.2e} loss_rel={e_loss:.2e}")
+    assert e_in <= TOL_ROWS and e_out <= TOL_ROWS and e_loss <= TOL_LOSS
+    # the tables are read-only for the gradient calculation
+    assert np.array_equal(_tables_to_host(d_in, dtype), Wi) and np.array_equal(_tables_to_host(d_out, dtype), Wo)
+    m.close()
+
+
+def test_sgns_grad_fresh_model_closed_form():
+    """W_out = 0: loss is (N+1) ln 2 whatever the batch, every Gin row is exactly zero."""
+    cfg = W.CONFIGS[1]
+    tok, counts = W.make_stream(cfg)
+    m = B.Model(cfg.vocab, cfg.dim, B.F32, cfg.window, cfg.negatives, cfg.batch, 0, cfg.seed, counts)
+    g = m.grad_buffers()
+    loss = torch.zeros(1, device="cuda")
+    m.sgns_grad(torch.from_numpy(tok).cuda(), 640, 64, 0, g, mean_loss=loss)
+    (ids_in, rows_in), _ = g.to_host()
+    assert abs(loss.item() - 6 * np.log(2.0)) < 1e-5
+    assert ids_in.size > 0 and not rows_in.any()
+    m.close()
+
+
+def test_empty_batches():
+    V, D = 50, 8
+    counts = np.ones(V, np.uint64)
+    m = B.Model(V, D, B.F32, 2, 3, 16, 0, 1, counts)
+    g = m.grad_buffers()
+    g.n_rows.fill_(99)
+    loss = torch.ones(1, device="cuda")
+    tok1 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    m.sgns_grad(tok1, 0, 1, 0, g, mean_loss=loss)                 # one token: a center without context
+    assert g.sizes() == (0, 0) and loss.item() == 0.0
+    g.n_rows.fill_(99)
+    tok = torch.arange(40, dtype=torch.int32, device="cuda")
+    m.sgns_grad(tok, 7, 0, 0, g)                                  # zero centers
+    assert g.sizes() == (0, 0)
+    before = m.w_in.clone()
+    m.dasgd_apply(g, [], 0.5)                                     # applying an empty gradient changes nothing
+    m.status()
+    assert torch.equal(before, m.w_in)
+    m.close()
+
+
+# ------------------------------------------------------------------ gradient application
+def _rand_sparse(rng, V, D, U):
+    ids = np.sort(rng.choice(V, size=U, replace=False)).astype(np.int32)
+    return ids, (rng.standard_normal((U, D)) * 0.1).astype(np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,D,stride,K,own", [(1000, 32, 32, 0, True), (4099, 300, 300, 3, True),
+                                              (4099, 300, 320, 7, True), (70_001, 128, 128, 15, True),
+                                              (513, 512, 512, 31, True), (2000, 64, 64, 4, False),
+                                              (63, 8, 8, 2, True)])
+def test_dasgd_apply_parity(dtype, V, D, stride, K, own):
+    _say("apply", dtype, V, D, stride, K, own)
+    bd, od, _, _ = DT[dtype]
+    rng = np.random.default_rng(V * 31 + K)
+    Wi, Wo = _random_tables(V, D, stride, dtype, seed=K + 1)
+    d_in, d_out = _tables_to_dev(Wi, dtype), _tables_to_dev(Wo, dtype)
+    m = B.Model(V, D, bd, 2, 3, 64, K, 1, np.ones(V, np.uint64), row_stride=stride, tables=(d_in, d_out))
+    srcs_in, srcs_out, bufs = [], [], []
+    for k in range(K + 1):
+        # mix of sizes: empty, single row, dense, first/last row of the vocabulary
+        Ui = [0, 1, V // 7, V // 2, V][k % 5] if k else max(V // 3, 1)
+        Uo = [V, V // 2, 1, 0, V // 5][k % 5] if k else max(V // 4, 1)
+        si, so = _rand_sparse(rng, V, D, Ui), _rand_sparse(rng, V, D, Uo)
+        gb = B.GradBuffers(max(Ui, 1) + 3, max(Uo, 1) + 5, D)
+        gb.load(si[0], si[1], so[0], so[1])
+        bufs.append(gb)
+        srcs_in.append(si)
+        srcs_out.append(so)
+    lr = 0.025
+    if own:
+        m.dasgd_apply(bufs[0], bufs[1:], lr)
+    else:
+        m.dasgd_apply(None, bufs[1:], lr)
+        srcs_in, srcs_out = srcs_in[1:], srcs_out[1:]
+    m.status()
+    Oi, Oo = Wi.copy(), Wo.copy()
+    oracle.dasgd_apply_table(Oi, D, od, srcs_in, lr)
+    oracle.dasgd_apply_table(Oo, D, od, srcs_out, lr)
+    for got_t, want, orig, srcs in ((d_in, Oi, Wi, srcs_in), (d_out, Oo, Wo, srcs_out)):
+        got = _tables_to_host(got_t, dtype)
+        touched = np.zeros(V, bool)
+        for ids, _ in srcs:
+            touched[ids] = True
+        # rows outside the union and all padding: bit-identical to the input
+        assert np.array_equal(got[~touched], orig[~touched])
+        assert np.array_equal(got[:, D:], orig[:, D:])
+        if dtype == "bf16":
+            d = bf16_ulp_dist(got, want)
+            _say(f"   bf16 max ulp distance {d}")
+            assert d <= BF16_ULP
+        else:
+            e = rel_l2(got, want)
+            ed = rel_l2(got.astype(np.float64) - orig, want.astype(np.float64) - orig)
+            _say(f"   table rel {e:.2e} delta rel {ed:.2e}")
+            assert e <= TOL_TABLE and ed <= TOL_DELTA
+            assert np.abs(got - want).max() <= 4 * np.finfo(np.float32).eps * max(1.0, np.abs(want).max())
+    m.close()
+
+
+def test_apply_is_eq1_and_merged_equals_sequential():
+    """K = 0 reproduces theta - alpha*g exactly (one fused multiply-add per element); merging K+1
+    gradients equals applying them one message at a time up to fp32 rounding (Algorithm 1)."""
+    V, D = 3000, 64
+    rng = np.random.default_rng(5)
+    Wi, Wo = _random_tables(V, D, D, "f32", seed=3)
+    srcs = [(_rand_sparse(rng, V, D, 900), _rand_sparse(rng, V, D, 1200)) for _ in range(4)]
+    bufs = []
+    for si, so in srcs:
+        gb = B.GradBuffers(900, 1200, D)
+        gb.load(si[0], si[1], so[0], so[1])
+        bufs.append(gb)
+    lr = np.float32(0.025)
+    a_in, a_out = _tables_to_dev(Wi, "f32"), _tables_to_dev(Wo, "f32")
+    m = B.Model(V, D, B.F32, 2, 3, 64, 3, 1, np.ones(V, np.uint64), tables=(a_in, a_out))
+    m.dasgd_apply(bufs[0], [], float(lr))
+    want = Wi.copy()
+    ids, rows = srcs[0][0]
+    want[ids] = (Wi[ids].astype(np.float64) - np.float64(lr) * rows.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(a_in.cpu().numpy(), want)          # Eq. 1, exactly rounded
+    for gb in bufs[1:]:
+        m.dasgd_apply(gb, [], float(lr))                      # one apply_gradient per message
+    b_in, b_out = _tables_to_dev(Wi, "f32"), _tables_to_dev(Wo, "f32")
+    m.rebind(b_in, b_out, 0)
+    m.dasgd_apply(bufs[0], bufs[1:], float(lr))               # merged
+    m.status()
+    assert rel_l2(b_in.cpu().numpy(), a_in.cpu().numpy()) < 1e-6
+    assert rel_l2(b_out.cpu().numpy(), a_out.cpu().numpy()) < 1e-6
+    m.close()
+
+
+# ------------------------------------------------------------------ multi-step runs (train)
+def _run_both(cfg, steps, threads=8):
+    tok, counts = W.make_stream(cfg)
+    gw = DasgdWorker(cfg, tok, counts)
+    ow = OracleWorker(cfg, tok, counts, threads=threads)
+    W0_in, W0_out = ow.W_in.copy(), ow.W_out.copy()
+    g_in0, g_out0 = gw.tables_to_host()
+    assert np.array_equal(g_in0, W0_in) and np.array_equal(g_out0, W0_out)     # same initial model, bit for bit
+    worst_rows = 0.0
+    for t in range(steps):
+        gw.step(want_loss=True)
+        grads = ow.step()
+        og = grads[0]
+        # per call: the own gradient
+        (ids_in, rows_in), (ids_out, rows_out) = gw.own.to_host()
+        assert np.array_equal(ids_in, og.gin.ids) and np.array_equal(ids_out, og.gout.ids), f"step {t}"
+        e = max(rows_rel(rows_in, og.gin.rows), rows_rel(rows_out, og.gout.rows))
+        worst_rows = max(worst_rows, e)
+        assert abs(gw.mean_loss.item() - og.loss) <= TOL_LOSS * og.loss, f"step {t}"
+        # peers: ids bit-exact as well (they were computed on the GPU from the GPU's own snapshots)
+        for k, pg in enumerate(grads[1:]):
+            ui, uo = gw.peer_bufs[k].sizes()
+            assert ui == pg.gin.ids.size and uo == pg.gout.ids.size, f"step {t} peer {k + 1}"
+        if cfg.peers and cfg.max_stale:
+            assert all(s % (cfg.peers + 1) == 0 for s in ow.last_staleness)
+    gw.model.status()
+    g_in, g_out = gw.tables_to_host()
+    _say(f"   {cfg.name}: {steps} steps, worst own-gradient row error {worst_rows:.2e}")
+    assert worst_rows <= TOL_ROWS
+    for got, want, w0, name in ((g_in, ow.W_in, W0_in, "W_in"), (g_out, ow.W_out, W0_out, "W_out")):
+        if cfg.dtype == "bf16":
+            d = bf16_ulp_dist(got, want)
+            moved = int((want != w0).sum())
+            _say(f"   {name}: bf16 max ulp distance {d}, elements moved {moved}")
+            assert d <= BF16_ULP and moved > 0
+        else:
+            e = rel_l2(got, want)
+            ed = rel_l2(got.astype(np.float64) - w0, want.astype(np.float64) - w0)
+            _say(f"   {name}: table rel {e:.2e}, delta rel {ed:.2e}")
+            assert e <= TOL_TABLE and ed <= TOL_DELTA
+    gw.model.close()
+    return gw, ow
+
+
+def test_train_config1_full_pass():
+    """Tiny SGNS, all 157 mini-batches of one pass (the last has 16 centers), single worker."""
+    _run_both(W.CONFIGS[1], 157, threads=1)
+
+
+@pytest.mark.parametrize("name,kw,steps", [
+    ("cfg2_small", dict(vocab=5_000, tokens=200_000, batch=256), 12),
+    ("cfg3_small", dict(vocab=20_000, tokens=300_000, batch=256), 8),
+    ("cfg4_small", dict(vocab=500, tokens=200_000, batch=1024), 4),
+    ("cfg5_small", dict(vocab=20_000, tokens=300_000, batch=256), 7),
+])
+def test_train_scaled_configs(name, kw, steps):
+    """The shapes of configurations 2-5 (dim, window, negatives, peers, staleness, dtype) at a vocabulary
+    and batch the oracle finishes in seconds; several radix/segment tiles and ragged tails."""
+    base = W.CONFIGS[int(name[3])]
+    _say("train", name)
+    _run_both(base.scaled(name=name, **kw), steps)
+
+
+@pytest.mark.parametrize("idx,steps", [(2, 6), (3, 5), (4, 2), (5, 2)])
+def test_train_full_size_configs(idx, steps):
+    """Configurations 2-5 at their full sizes, in the launch configuration the benchmark times."""
+    _say("train full size", idx)
+    _run_both(W.CONFIGS[idx], steps)
+
+
+# ------------------------------------------------------------------ error paths
+def test_errors_are_reported_not_faults():
+    V, D = 500, 16
+    m = B.Model(V, D, B.F32, 2, 3, 32, 2, 1, np.ones(V, np.uint64))
+    tok = torch.zeros(100, dtype=torch.int32, device="cuda")
+    g = m.grad_buffers()
+    with pytest.raises(B.TensairError) as e:
+        m.sgns_grad(tok, 90, 20, 0, g)                       # runs past the stream
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.TensairError) as e:
+        m.sgns_grad(tok, 0, 33, 0, g)                        # above max_centers
+    assert e.value.code == B.ECAPACITY
+    small = B.GradBuffers(4, 4, D)
+    with pytest.raises(B.TensairError) as e:
+        m.sgns_grad(tok, 0, 32, 0, small)                    # gradient buffers too small
+    assert e.value.code == B.ECAPACITY
+    with pytest.raises(B.TensairError) as e:
+        m.dasgd_apply(g, [g, g, g], 0.1)                     # above max_peers
+    assert e.value.code == B.ECAPACITY
+    # a peer gradient with unsorted / out-of-range ids: skipped safely, reported by status
+    bad = B.GradBuffers(8, 8, D)
+    bad.load(np.array([5, 3, 900], np.int32), np.ones((3, D), np.float32), np.array([1], np.int32),
+             np.ones((1, D), np.float32))
+    m.dasgd_apply(None, [bad], 0.1)
+    with pytest.raises(B.TensairError) as e:
+        m.status()
+    assert e.value.code == B.EDATA
+    m.status()                                               # the status word was cleared
+    m.close()
