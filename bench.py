@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of one DASGD worker step (tensair_step) on one MI355X.
+
+A "step" is one pass of the whole hot path over one mini-batch: pair enumeration, negative
+sampling, sort/segments, forward, segmented reductions (the own sparse gradient), then the
+merged application of the own gradient and the K peer gradients that are resident in HBM.
+
+Procedure
+  1. the synthetic workload of the chosen configuration is generated (Zipf token stream);
+  2. recording pass (untimed): warmup+steps worker steps are run while the K peer gradients of
+     every step -- computed with tensair_sgns_grad on the peers' own mini-batches against model
+     snapshots 0..max_stale steps old -- are stored compactly in HBM, and the algorithmic bytes
+     of every step are counted from the row counts;
+  3. the tables are reset to the initial model; warmup steps, then exactly `steps` calls of
+     tensair_step back to back on the stored peers, bracketed by torch.cuda.synchronize() and a
+     host clock; being deterministic, the replay computes exactly what the recording pass did;
+  4. the library's HIP-event hook times the table-update kernel (the dominant one) inside that
+     same timed region;
+  5. the CPU oracle is timed on the host for a bounded sample (one step's own gradient + apply).
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12  # bytes/s, MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 1M-vocab configuration the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build is the one-GPU worker step; there is no multi-GPU path (--gpus must be 1)")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2211_10280_amd import binding as B
+    from paper_2211_10280_amd import workload as W
+    from paper_2211_10280_amd.trainer import DasgdWorker
+
+    cfg = W.CONFIGS[args.config]
+    K, Wm, S = cfg.peers, args.warmup, args.steps
+    total = Wm + S
+    t0 = time.perf_counter()
+    tok, counts = W.make_stream(cfg)
+    log(f"[bench] workload {cfg.name}: stream of {cfg.tokens} tokens in {time.perf_counter() - t0:.1f}s")
+
+    worker = DasgdWorker(cfg, tok, counts)
+    model = worker.model
+    theta0 = (model.w_in.clone(), model.w_out.clone())
+    D, e = cfg.dim, cfg.elem_bytes
+
+    # ---- recording pass: peers of every step, algorithmic bytes
+    stored, bytes_grad, bytes_apply, pairs = [], [], [], []
+    for t in range(total):
+        peers = worker.make_peer_grads(t) if K else []
+        compact = []
+        for pb in peers:
+            ui, uo = pb.sizes()
+            cb = B.GradBuffers(ui, uo, D)
+            cb.in_ids[:ui].copy_(pb.in_ids[:ui]); cb.in_rows[:ui].copy_(pb.in_rows[:ui])
+            cb.out_ids[:uo].copy_(pb.out_ids[:uo]); cb.out_rows[:uo].copy_(pb.out_rows[:uo])
+            cb.n_rows.copy_(pb.n_rows)
+            compact.append(cb)
+        begin, n, epoch = worker.step(peers=compact)
+        stored.append(compact)
+        ui, uo = worker.own.sizes()
+        srcs_in = [worker.own.in_ids[:ui]] + [c.in_ids[: c.cap_in] for c in compact]
+        srcs_out = [worker.own.out_ids[:uo]] + [c.out_ids[: c.cap_out] for c in compact]
+        r_in = int(torch.unique(torch.cat(srcs_in)).numel())
+        r_out = int(torch.unique(torch.cat(srcs_out)).numel())
+        rows_all = sum(int(x.numel()) for x in srcs_in) + sum(int(x.numel()) for x in srcs_out)
+        bytes_grad.append((ui + uo) * D * e + (ui + uo) * D * 4)
+        bytes_apply.append(rows_all * D * 4 + 2 * (r_in + r_out) * D * e)
+        pairs.append(model.pair_count(cfg.tokens, begin, n))
+    model.status()
+    torch.cuda.synchronize()
+    log(f"[bench] recorded {total} steps; step {total - 1}: U_in={ui} U_out={uo} R_in={r_in} R_out={r_out} "
+        f"grad {bytes_grad[-1] / 1e6:.1f} MB apply {bytes_apply[-1] / 1e6:.1f} MB")
+
+    def reset():
+        model.w_in.copy_(theta0[0]); model.w_out.copy_(theta0[1])
+        worker.step_no = 0
+
+    # ---- replay: warmup, then the timed region
+    reset()
+    for t in range(Wm):
+        worker.step(peers=stored[t])
+    B.tensair_profile(model.h, 1)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for t in range(Wm, total):
+        worker.step(peers=stored[t])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    recs = B.tensair_profile_read(model.h)
+    B.tensair_profile(model.h, 0)
+    model.status()
+    apply_ms = [ms for tag, ms in recs if tag == "apply_update"]
+    assert len(apply_ms) == S, (len(apply_ms), S)
+
+    # ---- streaming ceiling of this machine: a plain 1 GiB copy (reads 1 GiB, writes 1 GiB)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.tensair_copy_probe(dst, src, nbytes)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(10):
+        B.tensair_copy_probe(dst, src, nbytes)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_GBps = 2 * nbytes * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
+    n_pairs = sum(pairs[Wm:])
+    value = n_pairs / elapsed
+    ms_per_step = elapsed / S * 1e3
+    step_bytes = sum(bytes_grad[Wm:]) + sum(bytes_apply[Wm:])
+    apply_bytes_per_launch = sum(bytes_apply[Wm:]) / S
+    apply_avg_s = (sum(apply_ms) / S) * 1e-3
+    achieved = apply_bytes_per_launch / apply_avg_s
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("k_apply_hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    breakdown = None
+    if args.breakdown:
+        reset()
+        B.tensair_profile(model.h, 2)
+        for t in range(total):
+            worker.step(peers=stored[t])
+            if t == Wm - 1:
+                B.tensair_profile_read(model.h)
+        torch.cuda.synchronize()
+        recs = B.tensair_profile_read(model.h)
+        B.tensair_profile(model.h, 0)
+        agg = {}
+        for tag, ms in recs:
+            agg[tag] = agg.get(tag, 0.0) + ms
+        breakdown = {k: round(v / S, 4) for k, v in agg.items()}
+        log("[bench] per-stage ms/step (events after every stage):", json.dumps(breakdown))
+
+    out = {
+        "metric": "training pairs/s per MI355X incl. DASGD apply; % of HBM roofline",
+        "value": value,
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": S,
+        "warmup": Wm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 tables, f32 accumulation",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "vocab": cfg.vocab, "dim": cfg.dim, "window": cfg.window,
+                   "negatives": cfg.negatives, "batch_centers": cfg.batch, "peers": K,
+                   "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S},
+        "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
+        "measured_copy_GBps": copy_GBps,
+        "step_algorithmic_bytes": step_bytes / S,
+        "roofline": {"bound": "hbm", "kernel": "k_apply", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": apply_bytes_per_launch,
+                     "avg_launch_ms": apply_avg_s * 1e3},
+    }
+    if breakdown:
+        out["stage_ms_per_step"] = breakdown
+
+    # ---- CPU baseline: the oracle as it stands, one core, a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        del stored, worker, theta0
+        torch.cuda.empty_cache()
+        from oracle.driver import OracleWorker
+
+        t0 = time.perf_counter()
+        ow = OracleWorker(cfg, tok, counts, threads=1)
+        n_cpu = {1: 157, 2: 12, 3: 4, 4: 1, 5: 1}[cfg.idx]
+        cpu_t, p_cpu = 0.0, 0
+        for t in range(n_cpu):
+            ow.step()
+            cpu_t += ow.t_own + ow.t_apply
+            p_cpu += W.pairs_in_batch(cfg, *W.worker_batch(cfg, t, 0)[:2])
+        log(f"[bench] oracle: {n_cpu} steps, own gradient + merged apply {cpu_t:.2f}s "
+            f"(whole leg incl. init and peer gradients {time.perf_counter() - t0:.1f}s)")
+        out["cpu_baseline"] = {"value": p_cpu / cpu_t, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+                               "sample": f"steps 0..{n_cpu - 1} of {cfg.name}: own gradient + merged apply of own and "
+                                         f"{K} peer gradients ({p_cpu} pairs, {cpu_t:.1f} s); peer gradient synthesis "
+                                         f"untimed, as on the GPU",
+                               "host_cpus": os.cpu_count()}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

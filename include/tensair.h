@@ -156,6 +156,22 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
  * status word) or TENSAIR_EHIP. */
 int tensair_status(tensair_model *m, void *stream);
 
+/* Stage timing with HIP events on the caller's stream (a measurement aid, not part of the
+ * method).  level 0: off (default); 1: one pair of events around the table-update kernel of
+ * tensair_dasgd_apply / tensair_step; 2: an event after every stage of the step.
+ * tensair_profile_read waits for the last recorded event, writes up to max_records
+ * (tag, milliseconds) records since the previous read and returns their number (negative =
+ * error).  Tags: 1 keys+negatives, 2 forward, 3 sort, 4 segments, 5 reduce W_in side,
+ * 6 reduce W_out side, 8 apply index, 9 apply table update; a tag's time runs from the
+ * previous event to its own.  At most 65536 events are kept between reads. */
+int tensair_profile(tensair_model *m, int level);
+int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max_records);
+
+/* Measurement aid: one plain copy kernel, dst[0..bytes) = src[0..bytes) (DEVICE, 16-byte
+ * aligned, bytes a multiple of 16, no overlap).  Reads `bytes` and writes `bytes`: the
+ * streaming-bandwidth ceiling of the box and the calibration of its HBM byte counters. */
+int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
 int tensair_model_destroy(tensair_model *m);
 
 const char *tensair_last_error(void);

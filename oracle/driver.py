@@ -9,6 +9,7 @@ counted in this worker's steps.
 """
 from __future__ import annotations
 
+import time
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -60,9 +61,15 @@ class OracleWorker:
         if self.threads > 1 and len(jobs) > 1:
             with ThreadPoolExecutor(self.threads) as ex:
                 grads = list(ex.map(lambda j: self._grad(*j), jobs))
+            self.t_own = float("nan")
         else:
-            grads = [self._grad(*j) for j in jobs]
+            t0 = time.perf_counter()
+            grads = [self._grad(*jobs[0])]
+            self.t_own = time.perf_counter() - t0            # the worker's own calculate_gradient
+            grads += [self._grad(*j) for j in jobs[1:]]      # what the other instances would have sent
+        t0 = time.perf_counter()
         oracle.dasgd_apply(self.W_in, self.W_out, c.dim, self.dtype, grads, c.lr)
+        self.t_apply = time.perf_counter() - t0
         self.applied |= {(t, k) for k in range(c.peers + 1)}
         self.last_own, self.last_peers = grads[0], grads[1:]
         self.step_no += 1

@@ -24,8 +24,11 @@ SYMBOLS = [
     "tensair_workspace_bytes", "tensair_capacity_in", "tensair_capacity_out", "tensair_model_init",
     "tensair_model_rebind", "tensair_model_alias", "tensair_pair_count", "tensair_sgns_grad",
     "tensair_dasgd_apply", "tensair_step", "tensair_status", "tensair_model_destroy",
-    "tensair_last_error",
+    "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
 ]
+
+PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
+                8: "apply_index", 9: "apply_update"}
 
 
 class TensairError(RuntimeError):
@@ -90,6 +93,12 @@ def lib():
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
         L.tensair_model_destroy.restype = C.c_int
+        L.tensair_profile.argtypes = [vp, C.c_int]
+        L.tensair_profile.restype = C.c_int
+        L.tensair_profile_read.argtypes = [vp, vp, vp, i32]
+        L.tensair_profile_read.restype = C.c_int
+        L.tensair_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
+        L.tensair_copy_probe.restype = C.c_int
         L.tensair_last_error.argtypes = []
         L.tensair_last_error.restype = C.c_char_p
         _lib = L
@@ -225,6 +234,24 @@ def tensair_step(h, tokens, center_begin: int, n_centers: int, epoch: int, peers
 
 def tensair_status(h, stream=None):
     _check(lib().tensair_status(h, _stream(stream)))
+
+
+def tensair_profile(h, level: int):
+    _check(lib().tensair_profile(h, level))
+
+
+def tensair_profile_read(h, max_records: int = 65536):
+    """[(tag name, milliseconds), ...] since the previous read."""
+    tags = np.zeros(max_records, dtype=np.int32)
+    ms = np.zeros(max_records, dtype=np.float32)
+    n = lib().tensair_profile_read(h, tags.ctypes.data_as(C.c_void_p), ms.ctypes.data_as(C.c_void_p), max_records)
+    if n < 0:
+        raise TensairError(n, lib().tensair_last_error().decode())
+    return [(PROFILE_TAGS.get(int(tags[i]), str(int(tags[i]))), float(ms[i])) for i in range(n)]
+
+
+def tensair_copy_probe(dst, src, nbytes: int, stream=None):
+    _check(lib().tensair_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
 def tensair_model_destroy(h):

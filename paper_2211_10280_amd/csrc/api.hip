@@ -105,6 +105,11 @@ struct tensair_model {
     u64 *mask[2];
     std::vector<uint32_t> h_thr;
     std::vector<int32_t> h_alias;
+    // stage timing (tensair_profile): events recorded on the caller's stream
+    int prof_level = 0;
+    std::vector<hipEvent_t> prof_pool;
+    std::vector<std::pair<int, hipEvent_t>> prof_marks;
+    size_t prof_used = 0;
 };
 
 namespace {
@@ -188,6 +193,26 @@ bool build_alias(const uint64_t *counts, i64 V, std::vector<uint32_t> &thr,
     }
     // whatever is left on either list keeps the full bucket (threshold max, alias = itself)
     return true;
+}
+
+// Stage tags of tensair_profile_read.  A tag's duration runs from the previous mark to its own.
+enum { PF_BEGIN_GRAD = 0, PF_KEYS, PF_FORWARD, PF_SORT, PF_SEGMENTS, PF_REDUCE_IN, PF_REDUCE_OUT,
+       PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE };
+
+void mark(tensair_model *m, int tag, hipStream_t st)
+{
+    if (m->prof_level == 0) return;
+    if (m->prof_level == 1 && tag != PF_APPLY_INDEX && tag != PF_APPLY_UPDATE) return;
+    if (m->prof_marks.size() >= 65536) return;
+    hipEvent_t ev;
+    if (m->prof_used < m->prof_pool.size()) {
+        ev = m->prof_pool[m->prof_used];
+    } else {
+        if (hipEventCreate(&ev) != hipSuccess) return;
+        m->prof_pool.push_back(ev);
+    }
+    ++m->prof_used;
+    if (hipEventRecord(ev, st) == hipSuccess) m->prof_marks.emplace_back(tag, ev);
 }
 
 i64 pair_count(const tensair_config &c, i64 T, i64 begin, int n)
@@ -343,10 +368,12 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     b.pair_base = pairs_before(center_begin, n_tokens, c.window);
     b.P = P;
 
+    mark(m, PF_BEGIN_GRAD, st);
     // 1. keys: out-side occurrences at [0, O), in-side centers at [Omax, Omax + n_centers)
     tn_launch_build_keys(b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, epoch, m->keys[0],
                          m->keys[0] + s.Omax, m->pair_center, negatives_dbg, m->status, st);
 
+    mark(m, PF_KEYS, st);
     // 2. forward on the unsorted keys (the sort below reuses their buffer): g per occurrence,
     //    per-center share of the W_in gradient, loss terms
     FwdArgs f;
@@ -365,6 +392,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     tn_launch_forward(f, st);
     if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
 
+    mark(m, PF_FORWARD, st);
     // 3. stable sort of both key lists by row id
     RadixProb ro, ri;
     for (int i = 0; i < 2; ++i) {
@@ -383,6 +411,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     ri.totals = m->totals_in;
     const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, st);
 
+    mark(m, PF_SORT, st);
     // 4. unique row ids, segment index per sorted entry
     SegProb so, si;
     so.keys = ro.keys[cur];
@@ -411,6 +440,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     si.weighted = 1;
     tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, st);
 
+    mark(m, PF_SEGMENTS, st);
     // 5. segmented reductions: duplicates of a row summed in sorted (= occurrence) order
     SegReduceArgs r;
     memset(&r, 0, sizeof(r));
@@ -423,6 +453,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.mode = 1;
     r.center_part = m->center_part;
     tn_launch_segreduce(r, st);
+    mark(m, PF_REDUCE_IN, st);
     r.n = (int)O;
     r.vals = so.vals;
     r.seg_of = so.seg_of;
@@ -436,6 +467,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.dtype = c.dtype;
     r.stride = c.row_stride;
     tn_launch_segreduce(r, st);
+    mark(m, PF_REDUCE_OUT, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }
@@ -484,7 +516,12 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const 
     if (own && (rc = fill_apply_src(a, 0, own, "own"))) return rc;
     for (int k = 0; k < n_peers; ++k)
         if ((rc = fill_apply_src(a, 1 + k, &peers[k], "peer"))) return rc;
-    tn_launch_apply(a, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    mark(m, PF_BEGIN_APPLY, st);
+    tn_launch_apply_index(a, st);
+    mark(m, PF_APPLY_INDEX, st);
+    tn_launch_apply_update(a, st);
+    mark(m, PF_APPLY_UPDATE, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }
@@ -528,8 +565,49 @@ int tensair_status(tensair_model *m, void *stream)
     return TENSAIR_OK;
 }
 
+int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15))
+        return fail(TENSAIR_EINVAL, "copy_probe: pointers and size must be multiples of 16");
+    tn_launch_copy_probe(dst, src, bytes, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_profile(tensair_model *m, int level)
+{
+    if (!m || level < 0 || level > 2) return fail(TENSAIR_EINVAL, "profile: bad argument");
+    m->prof_level = level;
+    return TENSAIR_OK;
+}
+
+int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max_records)
+{
+    if (!m || !tags || !ms || max_records < 0) return fail(TENSAIR_EINVAL, "profile_read: bad argument");
+    int n = 0;
+    if (!m->prof_marks.empty()) {
+        hipError_t e = hipEventSynchronize(m->prof_marks.back().second);
+        if (e != hipSuccess) return fail(TENSAIR_EHIP, "profile_read: %s", hipGetErrorString(e));
+    }
+    for (size_t i = 1; i < m->prof_marks.size() && n < max_records; ++i) {
+        const int tag = m->prof_marks[i].first;
+        if (tag == PF_BEGIN_GRAD || tag == PF_BEGIN_APPLY) continue;
+        if (m->prof_level == 1 && tag != PF_APPLY_UPDATE) continue;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, m->prof_marks[i - 1].second, m->prof_marks[i].second) != hipSuccess) continue;
+        tags[n] = tag;
+        ms[n] = t;
+        ++n;
+    }
+    m->prof_marks.clear();
+    m->prof_used = 0;
+    return n;
+}
+
 int tensair_model_destroy(tensair_model *m)
 {
+    if (m)
+        for (hipEvent_t ev : m->prof_pool) (void)hipEventDestroy(ev);
     delete m;
     return TENSAIR_OK;
 }

@@ -180,9 +180,9 @@ static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
     }
 }
 
-void tn_launch_apply(const ApplyArgs &a, hipStream_t st)
+void tn_launch_apply_index(const ApplyArgs &a, hipStream_t st)
 {
-    // index: enough blocks to cover the largest possible id list, grid-strided
+    // enough blocks to cover the largest possible id list, grid-strided
     i64 maxcap = 1;
     for (int tb = 0; tb < 2; ++tb)
         for (int k = 0; k < a.n_src; ++k)
@@ -190,6 +190,10 @@ void tn_launch_apply(const ApplyArgs &a, hipStream_t st)
     i64 want = (maxcap + 1 + BLOCK - 1) / BLOCK;
     int blocks = (int)(want > 1024 ? 1024 : want);
     hipLaunchKernelGGL(k_apply_index, dim3(blocks, a.n_src, 2), dim3(BLOCK), 0, st, a);
+}
+
+void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st)
+{
     if (a.dtype == 0) launch_apply_t<float>(a, st);
     else launch_apply_t<bf16_t>(a, st);
 }

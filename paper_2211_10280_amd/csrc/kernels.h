@@ -118,4 +118,8 @@ struct ApplyArgs {
     float lr;
     int *status;
 };
-void tn_launch_apply(const ApplyArgs &a, hipStream_t st);
+void tn_launch_apply_index(const ApplyArgs &a, hipStream_t st);
+void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st);
+
+// ---- measurement aid: plain copy of `bytes` (multiple of 16)
+void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);
