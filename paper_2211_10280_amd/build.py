@@ -28,7 +28,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every kernel and the host code into one shared library."""
     if not force and not stale():
         return LIB
-    cmd = ["hipcc", *FLAGS, "-o", LIB, *[os.path.join(CSRC, f) for f in SOURCES]]
+    extra = os.environ.get("TENSAIR_EXTRA_HIPCC_FLAGS", "").split()   # tuning experiments (-DNAME=value)
+    cmd = ["hipcc", *FLAGS, *extra, "-o", LIB, *[os.path.join(CSRC, f) for f in SOURCES]]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

@@ -79,8 +79,10 @@ Sizes sizes_of(const tensair_config &c)
     s.nblk_in = (int)((s.Bmax + TN_RADIX_TILE - 1) / TN_RADIX_TILE);
     s.sblk_out = (int)((s.Omax + TN_SCAN_TILE - 1) / TN_SCAN_TILE);
     s.sblk_in = (int)((s.Bmax + TN_SCAN_TILE - 1) / TN_SCAN_TILE);
-    s.tiles_out = (int)((s.Omax + TN_SEG_TILE - 1) / TN_SEG_TILE);
-    s.tiles_in = (int)((s.Bmax + TN_SEG_TILE - 1) / TN_SEG_TILE);
+    s.tiles_out = (int)((s.Omax + tn_seg_tile(s.Omax) - 1) / tn_seg_tile(s.Omax));   // worst case over n <= Omax
+    if (s.Omax > 65536 && s.tiles_out < 65536 / 8) s.tiles_out = 65536 / 8;
+    s.tiles_in = (int)((s.Bmax + tn_seg_tile(s.Bmax) - 1) / tn_seg_tile(s.Bmax));
+    if (s.Bmax > 65536 && s.tiles_in < 65536 / 8) s.tiles_in = 65536 / 8;
     s.words = (c.vocab + 63) / 64;
     return s;
 }
@@ -95,7 +97,7 @@ struct tensair_model {
     u32 *thr;
     int *alias;
     int *status;
-    u32 *keys[2], *vals[2];
+    u32 *keys[3], *vals[2];
     u32 *counts_out, *totals_out, *counts_in, *totals_in;
     int *seg_of;
     int *blk_heads, *blk_weight;
@@ -105,6 +107,10 @@ struct tensair_model {
     u64 *mask[2];
     std::vector<uint32_t> h_thr;
     std::vector<int32_t> h_alias;
+    // second stream for the part of the gradient calculation that does not depend on the forward
+    // pass (sort + segments); forked from and joined to the caller's stream with events
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // stage timing (tensair_profile): events recorded on the caller's stream
     int prof_level = 0;
     std::vector<hipEvent_t> prof_pool;
@@ -130,7 +136,7 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     p = take(V * 4); if (m) m->thr = (u32 *)p;
     p = take(V * 4); if (m) m->alias = (int *)p;
     p = take(256); if (m) m->status = (int *)p;
-    for (int i = 0; i < 2; ++i) { p = take(NE * 4); if (m) m->keys[i] = (u32 *)p; }
+    for (int i = 0; i < 3; ++i) { p = take(NE * 4); if (m) m->keys[i] = (u32 *)p; }
     for (int i = 0; i < 2; ++i) { p = take(NE * 4); if (m) m->vals[i] = (u32 *)p; }
     p = take((size_t)s.nd * s.nblk_out * 4); if (m) m->counts_out = (u32 *)p;
     p = take((size_t)s.nd * 4); if (m) m->totals_out = (u32 *)p;
@@ -298,6 +304,12 @@ int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_i
         delete m;
         return fail(TENSAIR_EHIP, "model_init: %s", hipGetErrorString(e));
     }
+    if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess) {
+        tensair_model_destroy(m);
+        return fail(TENSAIR_EHIP, "model_init: cannot create the side stream");
+    }
     *out = m;
     return TENSAIR_OK;
 }
@@ -374,7 +386,16 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
                          m->keys[0] + s.Omax, m->pair_center, negatives_dbg, m->status, st);
 
     mark(m, PF_KEYS, st);
-    // 2. forward on the unsorted keys (the sort below reuses their buffer): g per occurrence,
+    // The sort and the segment scan only need the keys, the forward pass only the keys and the
+    // tables: the two run side by side (second stream, fork/join by events) unless every stage
+    // is being timed, in which case they are serialised so that the stage times add up.
+    const bool overlap = m->prof_level < 2;
+    hipStream_t st2 = overlap ? m->side : st;
+    if (overlap) {
+        HIP_TRY(hipEventRecord(m->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+    }
+    // 2. forward on the unsorted keys (the sort never writes their buffer): g per occurrence,
     //    per-center share of the W_in gradient, loss terms
     FwdArgs f;
     f.w_in = m->w_in;
@@ -387,7 +408,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     f.out_keys = m->keys[0];
     f.g = m->g;
     f.center_part = m->center_part;
-    f.center_loss = m->center_loss;
+    f.center_loss = mean_loss ? m->center_loss : nullptr;   // loss terms only on request
     f.inv_P = 1.0f / (float)P;
     tn_launch_forward(f, st);
     if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
@@ -395,10 +416,12 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     mark(m, PF_FORWARD, st);
     // 3. stable sort of both key lists by row id
     RadixProb ro, ri;
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
         ro.keys[i] = m->keys[i];
-        ro.vals[i] = m->vals[i];
         ri.keys[i] = m->keys[i] + s.Omax;
+    }
+    for (int i = 0; i < 2; ++i) {
+        ro.vals[i] = m->vals[i];
         ri.vals[i] = m->vals[i] + s.Omax;
     }
     ro.n = (int)O;
@@ -409,12 +432,13 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     ri.nblk = (n_centers + TN_RADIX_TILE - 1) / TN_RADIX_TILE;
     ri.counts = m->counts_in;
     ri.totals = m->totals_in;
-    const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, st);
+    int kb = 1;
+    const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, st2, &kb);
 
     mark(m, PF_SORT, st);
     // 4. unique row ids, segment index per sorted entry
     SegProb so, si;
-    so.keys = ro.keys[cur];
+    so.keys = ro.keys[kb];
     so.vals = ro.vals[cur];
     so.n = (int)O;
     so.nblk = (int)((O + TN_SCAN_TILE - 1) / TN_SCAN_TILE);
@@ -426,7 +450,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     so.seg_offsets = seg_offsets_out;
     so.capacity = grad_out->out.capacity;
     so.weighted = 0;
-    si.keys = ri.keys[cur];
+    si.keys = ri.keys[kb];
     si.vals = ri.vals[cur];
     si.n = n_centers;
     si.nblk = (n_centers + TN_SCAN_TILE - 1) / TN_SCAN_TILE;
@@ -438,7 +462,11 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     si.seg_offsets = seg_offsets_in;
     si.capacity = grad_out->in.capacity;
     si.weighted = 1;
-    tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, st);
+    tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, st2);
+    if (overlap) {
+        HIP_TRY(hipEventRecord(m->ev_join, m->side));
+        HIP_TRY(hipStreamWaitEvent(st, m->ev_join, 0));
+    }
 
     mark(m, PF_SEGMENTS, st);
     // 5. segmented reductions: duplicates of a row summed in sorted (= occurrence) order
@@ -606,8 +634,12 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
 
 int tensair_model_destroy(tensair_model *m)
 {
-    if (m)
+    if (m) {
         for (hipEvent_t ev : m->prof_pool) (void)hipEventDestroy(ev);
+        if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+        if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+        if (m->side) (void)hipStreamDestroy(m->side);
+    }
     delete m;
     return TENSAIR_OK;
 }

@@ -46,6 +46,35 @@ __device__ __forceinline__ void st4(bf16_t *p, float4 v)
     *reinterpret_cast<uint2 *>(p) = r;
 }
 
+// Streaming variants: global address space (so that a pointer rebuilt from integers does not
+// fall back to flat addressing) and the non-temporal hint, for data that is touched once.
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef u32 v2u __attribute__((ext_vector_type(2)));
+#define GLOBAL_AS __attribute__((address_space(1)))
+__device__ __forceinline__ float4 ld4s(const float *p)
+{
+    v4f r = __builtin_nontemporal_load((const GLOBAL_AS v4f *)p);
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ float4 ld4s(const bf16_t *p)
+{
+    v2u r = __builtin_nontemporal_load((const GLOBAL_AS v2u *)p);
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ void st4s(float *p, float4 v)
+{
+    v4f r = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(r, (GLOBAL_AS v4f *)p);
+}
+__device__ __forceinline__ void st4s(bf16_t *p, float4 v)
+{
+    v2u r;
+    r.x = (u32)f32_to_bf16(v.x) | ((u32)f32_to_bf16(v.y) << 16);
+    r.y = (u32)f32_to_bf16(v.z) | ((u32)f32_to_bf16(v.w) << 16);
+    __builtin_nontemporal_store(r, (GLOBAL_AS v2u *)p);
+}
+
 // A row of D = 4*C4 elements is held by one wave: lane l owns chunks l, l+64, ...
 // (ITERS = ceil(C4/64) chunks per lane, compile-time).
 template <typename T, int ITERS>
@@ -64,6 +93,24 @@ __device__ __forceinline__ void store_row(T *row, const float4 (&r)[ITERS], int 
     for (int it = 0; it < ITERS; ++it) {
         int c = lane + WAVE * it;
         if (c < C4) st4(row + 4 * c, r[it]);
+    }
+}
+template <typename T, int ITERS>
+__device__ __forceinline__ void load_row_s(float4 (&r)[ITERS], const T *row, int C4, int lane)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        r[it] = (c < C4) ? ld4s(row + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+template <typename T, int ITERS>
+__device__ __forceinline__ void store_row_s(T *row, const float4 (&r)[ITERS], int C4, int lane)
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        if (c < C4) st4s(row + 4 * c, r[it]);
     }
 }
 template <int ITERS>
@@ -115,6 +162,23 @@ __device__ __forceinline__ float wave_sum(float x)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
     return x;
+}
+// The same sum with data-parallel-primitive moves instead of LDS-crossbar shuffles: four
+// in-row steps (16 lanes), then the row totals are chained into lane 63 and broadcast.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float x)
+{
+    x += dpp_get<0xB1, 0xF>(x);    // quad_perm [1,0,3,2]
+    x += dpp_get<0x4E, 0xF>(x);    // quad_perm [2,3,0,1]
+    x += dpp_get<0x141, 0xF>(x);   // row_half_mirror
+    x += dpp_get<0x140, 0xF>(x);   // row_mirror: every lane of a row holds the row's sum
+    x += dpp_get<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+    x += dpp_get<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 __device__ __forceinline__ u32 wave_or(u32 x)
 {

@@ -8,18 +8,23 @@
 //   forward   one workgroup per center position: the center row stays in registers, the
 //             context/negative rows are gathered once, g is stored per occurrence and the
 //             center's share of Gin is combined across waves through LDS;
-//   segreduce the occurrences sorted by row id are cut into fixed tiles of 64; a wave sums
+//   segreduce the occurrences sorted by row id are cut into fixed tiles (64, or 8 for small lists); a wave sums
 //             its tile in sorted order, writes rows that lie inside the tile directly and
 //             rows that cross a tile border as partials, which a second kernel chains in
 //             tile order.  Load balance is therefore independent of how hot a row is.
 #include "dev_common.h"
 #include "kernels.h"
 
-#define FWD_UNROLL 4
+#ifndef FWD_UNROLL
+#define FWD_UNROLL 2   // measured: 2 rows in flight per wave beat 4 and 8 (occupancy matters more)
+#endif
+#ifndef SEG_UNROLL
 #define SEG_UNROLL 4
+#endif
 
 // ---------------------------------------------------------------- forward
-template <typename T, int ITERS>
+// LOSS: also accumulate the loss terms (only when the caller asked for the mean loss).
+template <typename T, int ITERS, bool LOSS>
 __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
 {
     __shared__ float red[WAVES_PER_BLOCK][ITERS * WAVE * 4];
@@ -43,9 +48,11 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
     float4 v[ITERS], acc[ITERS];
     load_row<T, ITERS>(v, w_in + (size_t)c * a.stride, C4, lane);
     zero_row<ITERS>(acc);
-    float loss = 0.f;
+    float loss = 0.f;   // per-lane partial (lanes 0..FWD_UNROLL-1 carry it)
 
-    // wave `wave` takes tasks wave, wave+4, ...; FWD_UNROLL rows are in flight at a time
+    // wave `wave` takes tasks wave, wave+4, ...; FWD_UNROLL rows are in flight at a time.  The
+    // dot products are reduced one by one, then lane x evaluates the sigmoid of task x, so the
+    // transcendental code runs once per group instead of once per task.
     for (int t0 = wave; t0 < ntasks; t0 += WAVES_PER_BLOCK * FWD_UNROLL) {
         float4 u[FWD_UNROLL][ITERS];
 #pragma unroll
@@ -54,27 +61,32 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
             if (t < ntasks) {
                 u32 j = a.out_keys[occ0 + t];
                 load_row<T, ITERS>(u[x], w_out + (size_t)j * a.stride, C4, lane);
+            } else {
+                zero_row<ITERS>(u[x]);
             }
         }
+        float s_l = 0.f;
 #pragma unroll
         for (int x = 0; x < FWD_UNROLL; ++x) {
-            int t = t0 + x * WAVES_PER_BLOCK;
-            if (t < ntasks) {
-                float s = wave_sum(dot_partial<ITERS>(v, u[x]));
-                bool pos = (t % Np1) == 0;
-                // sigmoid(s) - label without cancellation:
-                //   label 1: -1/(1+e^s)      label 0: 1/(1+e^-s)
-                float z = pos ? s : -s;
-                float gg = 1.0f / (1.0f + expf(z));
-                gg = pos ? -gg : gg;
-                float g = gg * a.inv_P;
-                // loss term: softplus(-s) for the context, softplus(s) for a negative
-                float y = -z;
-                loss += fmaxf(y, 0.f) + log1pf(expf(-fabsf(y)));
-                if (lane == 0) a.g[occ0 + t] = g;
-                axpy_row<ITERS>(acc, g, u[x]);
-            }
+            float s = wave_sum_dpp(dot_partial<ITERS>(v, u[x]));
+            s_l = (lane == x) ? s : s_l;
         }
+        const int t_l = t0 + lane * WAVES_PER_BLOCK;
+        const bool live = (lane < FWD_UNROLL) && (t_l < ntasks);
+        const bool pos = (t_l % Np1) == 0;
+        // sigmoid(s) - label without cancellation: label 1: -1/(1+e^s), label 0: 1/(1+e^-s)
+        const float z = pos ? s_l : -s_l;
+        float gg = 1.0f / (1.0f + expf(z));
+        gg = pos ? -gg : gg;
+        const float g_l = live ? gg * a.inv_P : 0.f;
+        if (live) a.g[occ0 + t_l] = g_l;
+        if (LOSS) {
+            // loss term: softplus(-s) for the context, softplus(s) for a negative
+            const float y = -z;
+            if (live) loss += fmaxf(y, 0.f) + log1pf(expf(-fabsf(y)));
+        }
+#pragma unroll
+        for (int x = 0; x < FWD_UNROLL; ++x) axpy_row<ITERS>(acc, rd_lane(g_l, x), u[x]);
     }
     // combine the four waves in a fixed order
 #pragma unroll
@@ -85,7 +97,10 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
         red[wave][e + 2] = acc[it].z;
         red[wave][e + 3] = acc[it].w;
     }
-    if (lane == 0) lred[wave] = loss;
+    if (LOSS) {
+        loss = wave_sum_dpp(loss);
+        if (lane == 0) lred[wave] = loss;
+    }
     __syncthreads();
     float *dst = a.center_part + (size_t)i * a.D;
     for (int e = threadIdx.x; e < a.D; e += BLOCK) {
@@ -94,7 +109,7 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
         for (int w = 1; w < WAVES_PER_BLOCK; ++w) s += red[w][e];
         dst[e] = s;
     }
-    if (threadIdx.x == 0) {
+    if (LOSS && threadIdx.x == 0) {
         float s = lred[0];
 #pragma unroll
         for (int w = 1; w < WAVES_PER_BLOCK; ++w) s += lred[w];
@@ -102,24 +117,25 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
     }
 }
 
-template <typename T>
+template <typename T, bool LOSS>
 static void launch_forward_t(const FwdArgs &a, hipStream_t st)
 {
     int C4 = a.D / 4;
     int iters = (C4 + WAVE - 1) / WAVE;
     dim3 grid(a.b.n_centers), blk(BLOCK);
     switch (iters) {
-    case 1: hipLaunchKernelGGL((k_forward<T, 1>), grid, blk, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_forward<T, 2>), grid, blk, 0, st, a); break;
-    case 3: hipLaunchKernelGGL((k_forward<T, 3>), grid, blk, 0, st, a); break;
-    default: hipLaunchKernelGGL((k_forward<T, 4>), grid, blk, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_forward<T, 1, LOSS>), grid, blk, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_forward<T, 2, LOSS>), grid, blk, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((k_forward<T, 3, LOSS>), grid, blk, 0, st, a); break;
+    default: hipLaunchKernelGGL((k_forward<T, 4, LOSS>), grid, blk, 0, st, a); break;
     }
 }
 
 void tn_launch_forward(const FwdArgs &a, hipStream_t st)
 {
-    if (a.dtype == 0) launch_forward_t<float>(a, st);
-    else launch_forward_t<bf16_t>(a, st);
+    const bool loss = a.center_loss != nullptr;
+    if (a.dtype == 0) loss ? launch_forward_t<float, true>(a, st) : launch_forward_t<float, false>(a, st);
+    else loss ? launch_forward_t<bf16_t, true>(a, st) : launch_forward_t<bf16_t, false>(a, st);
 }
 
 // ---------------------------------------------------------------- segmented reduction
@@ -138,18 +154,18 @@ __device__ __forceinline__ void entry_source(const SegReduceArgs &a, u32 val, co
     }
 }
 
-// One wave per tile of TN_SEG_TILE sorted entries.  A row whose entries all lie in the
+// One wave per tile of TILE (<= 64) sorted entries.  A row whose entries all lie in the
 // tile is written to out_rows; the leading row if it continues from the previous tile
 // goes to part[tile][0], the trailing row if it continues into the next tile goes to
 // part[tile][1] (a row covering the whole tile and both borders counts as leading).
-template <typename T, int ITERS, int MODE>
+template <typename T, int ITERS, int MODE, int TILE>
 __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
 {
     const int tile = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
     const int lane = lane_id();
-    const int t0 = tile * TN_SEG_TILE;
+    const int t0 = tile * TILE;
     if (t0 >= a.n) return;
-    const int cnt = min(TN_SEG_TILE, a.n - t0);
+    const int cnt = min(TILE, a.n - t0);
     const int C4 = a.D >> 2;
 
     // lane l holds the metadata of entry t0 + l
@@ -210,15 +226,15 @@ __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
 // Chains the partials of rows that cross tile borders, in tile order.  One workgroup
 // per tile; it acts only if the tile's trailing row continues into the next tile and
 // started inside this tile (so every such row is owned by exactly one workgroup).
-template <int ITERS>
+template <int ITERS, int TILE>
 __global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
 {
     __shared__ float red[WAVES_PER_BLOCK][ITERS * WAVE * 4];
     __shared__ int s_len;
     const int tile = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = lane_id();
-    const int t0 = tile * TN_SEG_TILE;
-    const int t1 = min(a.n, t0 + TN_SEG_TILE);
+    const int t0 = tile * TILE;
+    const int t1 = min(a.n, t0 + TILE);
     if (t1 >= a.n) return;                        // last tile: nothing continues
     const int row = a.seg_of[t1 - 1];
     if (a.seg_of[t1] != row) return;              // trailing row ends at the border
@@ -233,7 +249,7 @@ __global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
             if (a.seg_of[mid] <= row) lo = mid + 1;
             else hi = mid;
         }
-        s_len = (lo - 1) / TN_SEG_TILE - tile;   // number of leading partials to add
+        s_len = (lo - 1) / TILE - tile;   // number of leading partials to add
     }
     __syncthreads();
     const int len = s_len;
@@ -273,30 +289,26 @@ __global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
     }
 }
 
+template <typename T, int MODE, int ITERS, int TILE>
+static void launch_segreduce_i(const SegReduceArgs &a, hipStream_t st)
+{
+    int ntiles = (a.n + TILE - 1) / TILE;
+    dim3 grid((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), blk(BLOCK);
+    hipLaunchKernelGGL((k_segreduce<T, ITERS, MODE, TILE>), grid, blk, 0, st, a);
+    if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), dim3(ntiles - 1), blk, 0, st, a);
+}
+
 template <typename T, int MODE>
 static void launch_segreduce_t(const SegReduceArgs &a, hipStream_t st)
 {
     int C4 = a.D / 4;
     int iters = (C4 + WAVE - 1) / WAVE;
-    int ntiles = (a.n + TN_SEG_TILE - 1) / TN_SEG_TILE;
-    dim3 grid((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), blk(BLOCK);
+    const bool small = tn_seg_tile(a.n) == 8;
     switch (iters) {
-    case 1:
-        hipLaunchKernelGGL((k_segreduce<T, 1, MODE>), grid, blk, 0, st, a);
-        if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<1>), dim3(ntiles - 1), blk, 0, st, a);
-        break;
-    case 2:
-        hipLaunchKernelGGL((k_segreduce<T, 2, MODE>), grid, blk, 0, st, a);
-        if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<2>), dim3(ntiles - 1), blk, 0, st, a);
-        break;
-    case 3:
-        hipLaunchKernelGGL((k_segreduce<T, 3, MODE>), grid, blk, 0, st, a);
-        if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<3>), dim3(ntiles - 1), blk, 0, st, a);
-        break;
-    default:
-        hipLaunchKernelGGL((k_segreduce<T, 4, MODE>), grid, blk, 0, st, a);
-        if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<4>), dim3(ntiles - 1), blk, 0, st, a);
-        break;
+    case 1: small ? launch_segreduce_i<T, MODE, 1, 8>(a, st) : launch_segreduce_i<T, MODE, 1, 64>(a, st); break;
+    case 2: small ? launch_segreduce_i<T, MODE, 2, 8>(a, st) : launch_segreduce_i<T, MODE, 2, 64>(a, st); break;
+    case 3: small ? launch_segreduce_i<T, MODE, 3, 8>(a, st) : launch_segreduce_i<T, MODE, 3, 64>(a, st); break;
+    default: small ? launch_segreduce_i<T, MODE, 4, 8>(a, st) : launch_segreduce_i<T, MODE, 4, 64>(a, st); break;
     }
 }
 

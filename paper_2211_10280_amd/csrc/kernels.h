@@ -9,7 +9,9 @@ typedef uint64_t u64;
 typedef int64_t i64;
 
 #define TN_MAX_SRC 32     // own + up to 31 peers
-#define TN_SEG_TILE 64    // sorted entries per wave in the segmented reduction
+// sorted entries per wave in the segmented reduction: small problems get small tiles so that
+// enough waves exist to hide the latency of the row loads
+static inline int tn_seg_tile(i64 n) { return n <= 65536 ? 8 : 64; }
 #define TN_RADIX_TILE 2048  // keys per block in a radix pass (256 threads x 8)
 #define TN_SCAN_TILE 2048   // entries per block in the head scan
 
@@ -33,15 +35,16 @@ void tn_launch_build_keys(const BatchDesc &b, i64 V, const u32 *thr, const int *
 
 // ---- stage 2: stable LSD radix sort of (key, value) for two independent problems at once
 struct RadixProb {
-    u32 *keys[2];   // ping-pong buffers; input in keys[0]
-    u32 *vals[2];   // values; the first pass writes the entry index (input order) itself
+    u32 *keys[3];   // input in keys[0], which is never written (other work may still read it);
+                    // the passes go 0 -> 1 -> 2 -> 1 -> ...
+    u32 *vals[2];   // values, ping-pong; the first pass writes the entry index (input order) itself
     int n;
     int nblk;       // ceil(n / TN_RADIX_TILE)
     u32 *counts;    // [2^bits][nblk] scratch
     u32 *totals;    // [2^bits] scratch
 };
-// returns which buffer (0/1) holds the sorted result
-int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st);
+// returns which vals buffer (0/1) holds the sorted values; *key_buf = which keys buffer (1/2)
+int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st, int *key_buf);
 
 // ---- stage 3: unique ids, segment index of every sorted entry, weighted segment offsets
 struct SegProb {

@@ -169,18 +169,20 @@ __global__ void __launch_bounds__(BLOCK) k_radix_scatter(RadixPass a)
     }
 }
 
-int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st)
+int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st, int *key_buf)
 {
     if (key_bits < 1) key_bits = 1;
     int passes = (key_bits + RADIX_MAX_BITS - 1) / RADIX_MAX_BITS;
     int bits = (key_bits + passes - 1) / passes;
     RadixProb p[2] = {p0, p1};
-    int cur = 0;
+    int cur = 0;    // vals buffer holding the current order
+    int kin = 0;    // keys buffer holding the current order
     for (int pass = 0; pass < passes; ++pass) {
+        const int kout = (kin == 1) ? 2 : 1;
         RadixPass a;
         for (int i = 0; i < 2; ++i) {
-            a.kin[i] = p[i].keys[cur];
-            a.kout[i] = p[i].keys[cur ^ 1];
+            a.kin[i] = p[i].keys[kin];
+            a.kout[i] = p[i].keys[kout];
             a.vin[i] = p[i].vals[cur];
             a.vout[i] = p[i].vals[cur ^ 1];
             a.n[i] = p[i].n;
@@ -198,7 +200,9 @@ int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t s
                            dim3(BLOCK), 0, st, a);
         hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(BLOCK), 0, st, a);
         cur ^= 1;
+        kin = kout;
     }
+    *key_buf = kin;
     return cur;
 }
 
