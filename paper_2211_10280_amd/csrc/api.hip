@@ -99,7 +99,7 @@ struct tensair_model {
     int *status;
     u32 *keys[3], *vals[2];
     u32 *counts_out, *totals_out, *counts_in, *totals_in;
-    int *seg_of;
+    int *seg_of, *seg_start;
     int *blk_heads, *blk_weight;
     int *pair_center;
     float *g, *center_part, *center_loss, *part_out, *part_in;
@@ -111,6 +111,10 @@ struct tensair_model {
     // pass (sort + segments); forked from and joined to the caller's stream with events
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // set by tensair_step: the index of the coming apply is built on the side stream as soon as
+    // the own row ids exist, next to the forward pass and the reductions
+    const ApplyArgs *fused_apply = nullptr;
+    bool fused_index_done = false;
     // stage timing (tensair_profile): events recorded on the caller's stream
     int prof_level = 0;
     std::vector<hipEvent_t> prof_pool;
@@ -143,6 +147,7 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     p = take((size_t)s.nd * s.nblk_in * 4); if (m) m->counts_in = (u32 *)p;
     p = take((size_t)s.nd * 4); if (m) m->totals_in = (u32 *)p;
     p = take(NE * 4); if (m) m->seg_of = (int *)p;
+    p = take((NE + 2) * 4); if (m) m->seg_start = (int *)p;   // out-side rows at 0, in-side at Omax+1
     p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_heads = (int *)p;
     p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_weight = (int *)p;
     p = take((size_t)s.Pmax * 4); if (m) m->pair_center = (int *)p;
@@ -445,6 +450,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     so.blk_heads = m->blk_heads;
     so.blk_weight = m->blk_weight;
     so.seg_of = m->seg_of;
+    so.seg_start = m->seg_start;
     so.row_ids = grad_out->out.row_ids;
     so.n_rows = grad_out->out.n_rows;
     so.seg_offsets = seg_offsets_out;
@@ -457,12 +463,17 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     si.blk_heads = m->blk_heads + s.sblk_out;
     si.blk_weight = m->blk_weight + s.sblk_out;
     si.seg_of = m->seg_of + s.Omax;
+    si.seg_start = m->seg_start + s.Omax + 1;
     si.row_ids = grad_out->in.row_ids;
     si.n_rows = grad_out->in.n_rows;
     si.seg_offsets = seg_offsets_in;
     si.capacity = grad_out->in.capacity;
     si.weighted = 1;
     tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, st2);
+    if (overlap && m->fused_apply) {
+        tn_launch_apply_index(*m->fused_apply, st2);
+        m->fused_index_done = true;
+    }
     if (overlap) {
         HIP_TRY(hipEventRecord(m->ev_join, m->side));
         HIP_TRY(hipStreamWaitEvent(st, m->ev_join, 0));
@@ -476,6 +487,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.n = n_centers;
     r.vals = si.vals;
     r.seg_of = si.seg_of;
+    r.seg_start = si.seg_start;
     r.out_rows = grad_out->in.row_grads;
     r.part = m->part_in;
     r.mode = 1;
@@ -485,6 +497,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.n = (int)O;
     r.vals = so.vals;
     r.seg_of = so.seg_of;
+    r.seg_start = so.seg_start;
     r.out_rows = grad_out->out.row_grads;
     r.part = m->part_out;
     r.mode = 0;
@@ -515,17 +528,14 @@ static int fill_apply_src(ApplyArgs &a, int k, const tensair_sparse_grad *g, con
     return TENSAIR_OK;
 }
 
-int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
-                        int32_t n_peers, float lr, void *stream)
+static int make_apply_args(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
+                           int32_t n_peers, float lr, ApplyArgs &a)
 {
-    if (!m) return fail(TENSAIR_EINVAL, "model is NULL");
     const tensair_config &c = m->cfg;
     if (n_peers < 0 || n_peers > c.max_peers)
         return fail(TENSAIR_ECAPACITY, "n_peers %d outside 0..max_peers %d", n_peers, c.max_peers);
     if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
     if (!(lr == lr)) return fail(TENSAIR_EINVAL, "lr is NaN");
-    if (!own && n_peers == 0) return TENSAIR_OK;
-    ApplyArgs a;
     memset(&a, 0, sizeof(a));
     a.table[0] = m->w_in;
     a.table[1] = m->w_out;
@@ -544,6 +554,17 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const 
     if (own && (rc = fill_apply_src(a, 0, own, "own"))) return rc;
     for (int k = 0; k < n_peers; ++k)
         if ((rc = fill_apply_src(a, 1 + k, &peers[k], "peer"))) return rc;
+    return TENSAIR_OK;
+}
+
+int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
+                        int32_t n_peers, float lr, void *stream)
+{
+    if (!m) return fail(TENSAIR_EINVAL, "model is NULL");
+    ApplyArgs a;
+    int rc = make_apply_args(m, own, peers, n_peers, lr, a);
+    if (rc) return rc;
+    if (!own && n_peers == 0) return TENSAIR_OK;
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_APPLY, st);
     tn_launch_apply_index(a, st);
@@ -558,21 +579,25 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
                  int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers, int32_t n_peers,
                  float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
 {
+    if (!m || !own_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     // validate the apply arguments before anything is enqueued
-    if (!m) return fail(TENSAIR_EINVAL, "model is NULL");
-    if (n_peers < 0 || n_peers > m->cfg.max_peers)
-        return fail(TENSAIR_ECAPACITY, "n_peers %d outside 0..max_peers %d", n_peers, m->cfg.max_peers);
-    if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
-    for (int k = 0; k < n_peers; ++k) {
-        const tensair_sparse_rows *side[2] = {&peers[k].in, &peers[k].out};
-        for (int t = 0; t < 2; ++t)
-            if (!side[t]->n_rows || !side[t]->row_ids || !side[t]->row_grads)
-                return fail(TENSAIR_EINVAL, "peer %d: NULL pointer", k);
-    }
-    int rc = tensair_sgns_grad(m, tokens, n_tokens, center_begin, n_centers, epoch, own_out, mean_loss,
-                               nullptr, nullptr, nullptr, stream);
+    ApplyArgs a;
+    int rc = make_apply_args(m, own_out, peers, n_peers, lr, a);
     if (rc) return rc;
-    return tensair_dasgd_apply(m, own_out, peers, n_peers, lr, stream);
+    m->fused_apply = &a;
+    m->fused_index_done = false;
+    rc = tensair_sgns_grad(m, tokens, n_tokens, center_begin, n_centers, epoch, own_out, mean_loss, nullptr,
+                           nullptr, nullptr, stream);
+    m->fused_apply = nullptr;
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    mark(m, PF_BEGIN_APPLY, st);
+    if (!m->fused_index_done) tn_launch_apply_index(a, st);
+    mark(m, PF_APPLY_INDEX, st);
+    tn_launch_apply_update(a, st);
+    mark(m, PF_APPLY_UPDATE, st);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
 }
 
 int tensair_status(tensair_model *m, void *stream)
@@ -592,6 +617,15 @@ int tensair_status(tensair_model *m, void *stream)
     }
     return TENSAIR_OK;
 }
+
+#ifdef TENSAIR_DEBUG
+extern "C" int tensair_debug_ptrs(tensair_model *m, void **out)
+{
+    out[0] = m->part_out; out[1] = m->part_in; out[2] = m->seg_of; out[3] = m->seg_start;
+    out[4] = m->vals[0]; out[5] = m->vals[1]; out[6] = m->g; out[7] = m->pair_center;
+    return 0;
+}
+#endif
 
 int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
 {

@@ -51,7 +51,7 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a)
     const int lane = lane_id();
     const int V = (int)a.V;
     // wave-uniform trip count: every lane takes part in the shuffles
-    for (int base = (blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6)) * WAVE; base < U;
+    for (int base = (blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6))) * WAVE; base < U;
          base += gridDim.x * BLOCK) {
         const int i = base + lane;
         const bool valid = i < U;
@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(BLOCK) k_apply(ApplyArgs a, int nblocks)
         }
     }
     constexpr int GPW = 64 / G;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int gw = bid * WAVES_PER_BLOCK + wave;
     const int word = gw / GPW, sub = gw - word * GPW;
     const int words = (int)((a.V + 63) >> 6);
@@ -210,7 +210,7 @@ __global__ void __launch_bounds__(BLOCK) k_apply(ApplyArgs a, int nblocks)
 template <typename T, int ITERS, int G>
 __global__ void __launch_bounds__(BLOCK) k_apply_persist(ApplyArgs a, int ngroups)
 {
-    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int nblocks = gridDim.x;
     const int nwaves = nblocks * WAVES_PER_BLOCK;
     // workgroups are dealt round-robin to the 8 XCDs: give every XCD a contiguous share of each

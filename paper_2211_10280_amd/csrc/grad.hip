@@ -8,10 +8,10 @@
 //   forward   one workgroup per center position: the center row stays in registers, the
 //             context/negative rows are gathered once, g is stored per occurrence and the
 //             center's share of Gin is combined across waves through LDS;
-//   segreduce the occurrences sorted by row id are cut into fixed tiles (64, or 8 for small lists); a wave sums
-//             its tile in sorted order, writes rows that lie inside the tile directly and
-//             rows that cross a tile border as partials, which a second kernel chains in
-//             tile order.  Load balance is therefore independent of how hot a row is.
+//   segreduce the occurrences sorted by row id are cut into fixed tiles (32, or 8 for small lists);
+//             a wave sums, in sorted order, the short rows that begin in its tile and its share
+//             of long rows, whose partials a second kernel chains in tile order.  Load balance
+//             is therefore independent of how hot a row is.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -30,7 +30,7 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
     __shared__ float red[WAVES_PER_BLOCK][ITERS * WAVE * 4];
     __shared__ float lred[WAVES_PER_BLOCK];
     const int i = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int C4 = a.D >> 2;
     const BatchDesc &b = a.b;
     const i64 p = b.begin + i;
@@ -154,47 +154,91 @@ __device__ __forceinline__ void entry_source(const SegReduceArgs &a, u32 val, co
     }
 }
 
-// One wave per tile of TILE (<= 64) sorted entries.  A row whose entries all lie in the
-// tile is written to out_rows; the leading row if it continues from the previous tile
-// goes to part[tile][0], the trailing row if it continues into the next tile goes to
-// part[tile][1] (a row covering the whole tile and both borders counts as leading).
+// One wave per tile of TILE (<= 32) sorted entries.  A row (segment) of at most TILE entries is
+// "short": it is summed completely, in sorted order, by the wave whose tile contains its first
+// entry, even where it runs into the next tile, and written once.  Longer rows are "long": every
+// tile sums the part of the row that lies inside it into a partial (part[tile][0] for a row that
+// began in an earlier tile, part[tile][1] for one that begins here), and k_segfixup chains the
+// partials in tile order.  Work per wave is bounded by 2*TILE entries whatever the skew of the ids.
 template <typename T, int ITERS, int MODE, int TILE>
 __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
 {
-    const int tile = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    static_assert(2 * TILE <= WAVE, "a wave keeps the metadata of two tiles in its lanes");
+    // the wave index is made explicitly wave-uniform so that all the control flow below is scalar
+    const int tile = blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int t0 = tile * TILE;
     if (t0 >= a.n) return;
-    const int cnt = min(TILE, a.n - t0);
+    const int t1 = min(a.n, t0 + TILE);
     const int C4 = a.D >> 2;
 
-    // lane l holds the metadata of entry t0 + l
+    // lane l holds the metadata of entry t0 + l, for this tile and the next
+    const int avail = min(2 * TILE, a.n - t0);
     int seg_l = -1;
     u32 val_l = 0;
-    if (lane < cnt) {
+    if (lane < avail) {
         seg_l = a.seg_of[t0 + lane];
         val_l = a.vals[t0 + lane];
     }
     const T *row_l = nullptr;
     float scale_l = 0.f;
-    if (lane < cnt) entry_source<T, ITERS, MODE>(a, val_l, row_l, scale_l);
-    const int seg_before = (t0 > 0) ? a.seg_of[t0 - 1] : -1;
-    const int seg_after = (t0 + cnt < a.n) ? a.seg_of[t0 + cnt] : -2;
+    if (lane < avail) entry_source<T, ITERS, MODE>(a, val_l, row_l, scale_l);
 
-    int cur = rd_lane(seg_l, 0);
-    bool open_left = (cur == seg_before);   // current row started in an earlier tile
+    // heads inside the two-tile window (bit l: entry t0+l opens a row); bit `avail` closes the list
+    const int seg_up = __shfl_up(seg_l, 1, WAVE);
+    const int first_row = rd_lane(seg_l, 0);
+    const int first_start = a.seg_start[first_row];          // the only dependent load of the wave
+    const bool head_l = (lane < avail) && (lane == 0 ? (first_start == t0) : (seg_l != seg_up));
+    const u64 heads = __ballot(head_l);
+    const bool at_end = (t0 + avail == a.n);                 // the window reaches the end of the list
+    // end (relative) of the row whose first entry in the window is at e, or -1 if it runs past the window
+    auto row_end = [&](int e) -> int {
+        const u64 later = (e + 1 < 64) ? (heads >> (e + 1)) : 0ull;
+        if (later) return e + 1 + (int)__builtin_ctzll(later);
+        return at_end ? avail : -1;
+    };
+    const int tile_len = t1 - t0;
+    // range of entries this wave sums: from the first row it owns (or its share of a long row that
+    // began earlier) to the end of the last row that begins in the tile (or the tile end if long)
+    int e_begin = 0, e_end;
+    int dest = 0;                    // of the current row: 0 out_rows, 1 part[tile][0], 2 part[tile][1]
+    {
+        const int fe = row_end(0);
+        const bool lead_long = (fe < 0) || (t0 + fe - first_start) > TILE;
+        if (first_start < t0) {
+            if (lead_long) dest = 1;
+            else e_begin = fe;                          // short row owned by an earlier tile
+        } else {
+            dest = lead_long ? 2 : 0;
+        }
+        const u64 in_tile = heads & ((tile_len < 64) ? ((1ull << tile_len) - 1ull) : ~0ull);
+        if (in_tile) {
+            const int h_last = 63 - (int)__builtin_clzll(in_tile);
+            const int end = row_end(h_last);
+            const bool is_long = (end < 0) || (end - h_last) > TILE;
+            e_end = is_long ? tile_len : end;
+        } else {
+            e_end = (first_start < t0 && lead_long) ? tile_len : e_begin;
+        }
+    }
+    if (e_begin >= e_end) return;
     float4 acc[ITERS];
     zero_row<ITERS>(acc);
     float *part = a.part + (size_t)tile * 2 * a.D;
+    int cur = rd_lane(seg_l, e_begin);
+    if (e_begin > 0) {   // the first owned row begins at e_begin
+        const int end = row_end(e_begin);
+        dest = ((end < 0) || (end - e_begin) > TILE) ? 2 : 0;
+    }
 
-    for (int e0 = 0; e0 < cnt; e0 += SEG_UNROLL) {
+    for (int e0 = e_begin; e0 < e_end; e0 += SEG_UNROLL) {
         float4 r[SEG_UNROLL][ITERS];
         float sc[SEG_UNROLL];
         int sg[SEG_UNROLL];
 #pragma unroll
         for (int x = 0; x < SEG_UNROLL; ++x) {
-            int e = e0 + x;
-            if (e < cnt) {
+            const int e = e0 + x;
+            if (e < e_end) {
                 sg[x] = rd_lane(seg_l, e);
                 sc[x] = rd_lane(scale_l, e);
                 const T *row = (const T *)rd_lane64((u64)row_l, e);
@@ -203,89 +247,86 @@ __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
         }
 #pragma unroll
         for (int x = 0; x < SEG_UNROLL; ++x) {
-            int e = e0 + x;
-            if (e < cnt) {
-                if (sg[x] != cur) {   // the row `cur` ends inside this tile
-                    float *dst = open_left ? part : a.out_rows + (size_t)cur * a.D;
+            const int e = e0 + x;
+            if (e < e_end) {
+                if (sg[x] != cur) {   // row `cur` is complete (or its share of it): write it out
+                    float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
                     store_row<float, ITERS>(dst, acc, C4, lane);
                     zero_row<ITERS>(acc);
-                    open_left = false;
                     cur = sg[x];
+                    const int end = row_end(e);
+                    dest = ((end < 0) || (end - e) > TILE) ? 2 : 0;
                 }
                 axpy_row<ITERS>(acc, sc[x], r[x]);
             }
         }
     }
-    {
-        bool open_right = (cur == seg_after);
-        float *dst = open_left ? part : (open_right ? part + a.D : a.out_rows + (size_t)cur * a.D);
-        store_row<float, ITERS>(dst, acc, C4, lane);
-    }
+    float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
+    store_row<float, ITERS>(dst, acc, C4, lane);
 }
 
-// Chains the partials of rows that cross tile borders, in tile order.  One workgroup
-// per tile; it acts only if the tile's trailing row continues into the next tile and
-// started inside this tile (so every such row is owned by exactly one workgroup).
+// Chains the partials of long rows in tile order.  One wave looks at one tile: if the tile's last
+// row is long and begins in this tile, the workgroup sums part[tile][1] and the leading partials
+// part[t][0] of the following tiles the row covers, four waves sharing the chain.
 template <int ITERS, int TILE>
 __global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
 {
     __shared__ float red[WAVES_PER_BLOCK][ITERS * WAVE * 4];
-    __shared__ int s_len;
-    const int tile = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
-    const int t0 = tile * TILE;
-    const int t1 = min(a.n, t0 + TILE);
-    if (t1 >= a.n) return;                        // last tile: nothing continues
-    const int row = a.seg_of[t1 - 1];
-    if (a.seg_of[t1] != row) return;              // trailing row ends at the border
-    const bool started_before = (t0 > 0) && (a.seg_of[t0 - 1] == row) && (a.seg_of[t0] == row);
-    if (started_before) return;                   // owned by the tile where the row starts
-    // the chain: part[tile][1], then part[t][0] for t = tile+1 .. last tile holding `row`;
-    // the entries are sorted, so the end of the row is found by bisection
-    if (threadIdx.x == 0) {
-        int lo = t1, hi = a.n;   // first index in [t1, n) whose row index exceeds `row`
-        while (lo < hi) {
-            int mid = lo + ((hi - lo) >> 1);
-            if (a.seg_of[mid] <= row) lo = mid + 1;
-            else hi = mid;
-        }
-        s_len = (lo - 1) / TILE - tile;   // number of leading partials to add
-    }
-    __syncthreads();
-    const int len = s_len;
+    __shared__ int s_row[WAVES_PER_BLOCK], s_len[WAVES_PER_BLOCK];
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int C4 = a.D >> 2;
-    float4 acc[ITERS];
-    zero_row<ITERS>(acc);
-    if (wave == 0) load_row<float, ITERS>(acc, a.part + ((size_t)tile * 2 + 1) * a.D, C4, lane);
-    // wave w adds the leading partials of tiles tile+1+w, tile+1+w+4, ...
-    for (int j0 = wave; j0 < len; j0 += WAVES_PER_BLOCK * SEG_UNROLL) {
-        float4 r[SEG_UNROLL][ITERS];
-#pragma unroll
-        for (int x = 0; x < SEG_UNROLL; ++x) {
-            int j = j0 + x * WAVES_PER_BLOCK;
-            if (j < len) load_row<float, ITERS>(r[x], a.part + (size_t)(tile + 1 + j) * 2 * a.D, C4, lane);
+    {
+        const int tile = blockIdx.x * WAVES_PER_BLOCK + wave;
+        const int t0 = tile * TILE;
+        int row = -1, len = 0;
+        if (t0 < a.n) {
+            const int t1 = min(a.n, t0 + TILE);
+            const int r = a.seg_of[t1 - 1];
+            const int start = a.seg_start[r], end = a.seg_start[r + 1];
+            if (start >= t0 && (end - start) > TILE) {
+                row = r;
+                len = (end - 1) / TILE - tile;   // tiles after this one that hold a leading partial
+            }
         }
-#pragma unroll
-        for (int x = 0; x < SEG_UNROLL; ++x) {
-            int j = j0 + x * WAVES_PER_BLOCK;
-            if (j < len) add_row<ITERS>(acc, r[x]);
-        }
-    }
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        int e = (lane + WAVE * it) * 4;
-        red[wave][e + 0] = acc[it].x;
-        red[wave][e + 1] = acc[it].y;
-        red[wave][e + 2] = acc[it].z;
-        red[wave][e + 3] = acc[it].w;
+        if (lane == 0) { s_row[wave] = row; s_len[wave] = len; }
     }
     __syncthreads();
-    float *dst = a.out_rows + (size_t)row * a.D;
-    for (int e = threadIdx.x; e < a.D; e += BLOCK) {
-        float s = red[0][e];
+    for (int q = 0; q < WAVES_PER_BLOCK; ++q) {
+        const int row = s_row[q];
+        if (row < 0) continue;                       // uniform over the workgroup
+        const int tile = blockIdx.x * WAVES_PER_BLOCK + q;
+        const int len = s_len[q];
+        float4 acc[ITERS];
+        zero_row<ITERS>(acc);
+        if (wave == 0) load_row<float, ITERS>(acc, a.part + ((size_t)tile * 2 + 1) * a.D, C4, lane);
+        for (int j0 = wave; j0 < len; j0 += WAVES_PER_BLOCK * SEG_UNROLL) {
+            float4 r[SEG_UNROLL][ITERS];
 #pragma unroll
-        for (int w = 1; w < WAVES_PER_BLOCK; ++w) s += red[w][e];
-        dst[e] = s;
+            for (int x = 0; x < SEG_UNROLL; ++x) {
+                int j = j0 + x * WAVES_PER_BLOCK;
+                if (j < len) load_row<float, ITERS>(r[x], a.part + (size_t)(tile + 1 + j) * 2 * a.D, C4, lane);
+                else zero_row<ITERS>(r[x]);
+            }
+#pragma unroll
+            for (int x = 0; x < SEG_UNROLL; ++x) add_row<ITERS>(acc, r[x]);
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            int e = (lane + WAVE * it) * 4;
+            red[wave][e + 0] = acc[it].x;
+            red[wave][e + 1] = acc[it].y;
+            red[wave][e + 2] = acc[it].z;
+            red[wave][e + 3] = acc[it].w;
+        }
+        __syncthreads();
+        float *dst = a.out_rows + (size_t)row * a.D;
+        for (int e = threadIdx.x; e < a.D; e += BLOCK) {
+            float s = red[0][e];
+#pragma unroll
+            for (int w = 1; w < WAVES_PER_BLOCK; ++w) s += red[w][e];
+            dst[e] = s;
+        }
+        __syncthreads();
     }
 }
 
@@ -295,7 +336,7 @@ static void launch_segreduce_i(const SegReduceArgs &a, hipStream_t st)
     int ntiles = (a.n + TILE - 1) / TILE;
     dim3 grid((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), blk(BLOCK);
     hipLaunchKernelGGL((k_segreduce<T, ITERS, MODE, TILE>), grid, blk, 0, st, a);
-    if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), dim3(ntiles - 1), blk, 0, st, a);
+    if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), grid, blk, 0, st, a);
 }
 
 template <typename T, int MODE>
@@ -305,10 +346,10 @@ static void launch_segreduce_t(const SegReduceArgs &a, hipStream_t st)
     int iters = (C4 + WAVE - 1) / WAVE;
     const bool small = tn_seg_tile(a.n) == 8;
     switch (iters) {
-    case 1: small ? launch_segreduce_i<T, MODE, 1, 8>(a, st) : launch_segreduce_i<T, MODE, 1, 64>(a, st); break;
-    case 2: small ? launch_segreduce_i<T, MODE, 2, 8>(a, st) : launch_segreduce_i<T, MODE, 2, 64>(a, st); break;
-    case 3: small ? launch_segreduce_i<T, MODE, 3, 8>(a, st) : launch_segreduce_i<T, MODE, 3, 64>(a, st); break;
-    default: small ? launch_segreduce_i<T, MODE, 4, 8>(a, st) : launch_segreduce_i<T, MODE, 4, 64>(a, st); break;
+    case 1: small ? launch_segreduce_i<T, MODE, 1, 8>(a, st) : launch_segreduce_i<T, MODE, 1, 32>(a, st); break;
+    case 2: small ? launch_segreduce_i<T, MODE, 2, 8>(a, st) : launch_segreduce_i<T, MODE, 2, 32>(a, st); break;
+    case 3: small ? launch_segreduce_i<T, MODE, 3, 8>(a, st) : launch_segreduce_i<T, MODE, 3, 32>(a, st); break;
+    default: small ? launch_segreduce_i<T, MODE, 4, 8>(a, st) : launch_segreduce_i<T, MODE, 4, 32>(a, st); break;
     }
 }
 

@@ -11,7 +11,7 @@ typedef int64_t i64;
 #define TN_MAX_SRC 32     // own + up to 31 peers
 // sorted entries per wave in the segmented reduction: small problems get small tiles so that
 // enough waves exist to hide the latency of the row loads
-static inline int tn_seg_tile(i64 n) { return n <= 65536 ? 8 : 64; }
+static inline int tn_seg_tile(i64 n) { return n <= 65536 ? 8 : 32; }
 #define TN_RADIX_TILE 2048  // keys per block in a radix pass (256 threads x 8)
 #define TN_SCAN_TILE 2048   // entries per block in the head scan
 
@@ -55,6 +55,7 @@ struct SegProb {
     int *blk_heads;       // [nblk] scratch
     int *blk_weight;      // [nblk] scratch
     int *seg_of;          // [n] out: row index (0..U-1) of every sorted entry
+    int *seg_start;       // [U+1] out: index of the first sorted entry of every row, then n
     int *row_ids;         // [capacity] out
     int *n_rows;          // [1] out
     int *seg_offsets;     // [U+1] out or NULL
@@ -82,6 +83,7 @@ struct SegReduceArgs {
     int n;                 // sorted entries
     const u32 *vals;       // sorted values
     const int *seg_of;     // row index per sorted entry
+    const int *seg_start;  // first sorted entry of every row; [U] = n
     float *out_rows;       // [U][D]
     float *part;           // [ntiles][2][D] scratch for rows that cross tile borders
     int D;

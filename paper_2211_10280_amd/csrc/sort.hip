@@ -310,6 +310,7 @@ __global__ void __launch_bounds__(BLOCK) k_seg_assign(SegPass a)
             run_h += hd[j];
             int seg = run_h - 1;
             p.seg_of[i] = seg;
+            if (hd[j]) p.seg_start[seg] = i;
             if (hd[j]) {
                 if ((i64)seg < p.capacity) {
                     p.row_ids[seg] = (int)key[j];
@@ -320,6 +321,7 @@ __global__ void __launch_bounds__(BLOCK) k_seg_assign(SegPass a)
             }
             run_w += wt[j];
             if (i == p.n - 1) {
+                p.seg_start[seg + 1] = p.n;
                 int U = seg + 1;
                 if ((i64)U > p.capacity) U = (int)p.capacity;
                 *p.n_rows = U;
