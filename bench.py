@@ -42,8 +42,8 @@ def log(*a):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 20 for workload 3; 100/50/10/6 for 1/2/4/5)")
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 1M-vocab configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
@@ -60,6 +60,10 @@ def main():
     from paper_2211_10280_amd.trainer import DasgdWorker
 
     cfg = W.CONFIGS[args.config]
+    if args.steps is None:
+        args.steps = {1: 100, 2: 50, 3: 20, 4: 10, 5: 6}[cfg.idx]   # bounded by the HBM the stored peers take
+    if args.warmup is None:
+        args.warmup = 2 if cfg.idx == 5 else 3
     K, Wm, S = cfg.peers, args.warmup, args.steps
     total = Wm + S
     t0 = time.perf_counter()
