@@ -121,8 +121,9 @@ def main():
     recs = B.tensair_profile_read(model.h)
     B.tensair_profile(model.h, 0)
     model.status()
-    apply_ms = [ms for tag, ms in recs if tag == "apply_update"]
+    apply_ms = [ms for tag, ms in recs if tag == "apply_update"]   # one launch of k_apply per step
     assert len(apply_ms) == S, (len(apply_ms), S)
+    n_launch = len(apply_ms)
 
     # ---- streaming ceiling of this machine: a plain 1 GiB copy (reads 1 GiB, writes 1 GiB)
     nbytes = 1 << 30
@@ -143,15 +144,15 @@ def main():
     value = n_pairs / elapsed
     ms_per_step = elapsed / S * 1e3
     step_bytes = sum(bytes_grad[Wm:]) + sum(bytes_apply[Wm:])
-    apply_bytes_per_launch = sum(bytes_apply[Wm:]) / S
-    apply_avg_s = (sum(apply_ms) / S) * 1e-3
+    apply_bytes_per_launch = sum(bytes_apply[Wm:]) / n_launch
+    apply_avg_s = (sum(apply_ms) / n_launch) * 1e-3
     achieved = apply_bytes_per_launch / apply_avg_s
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("k_apply_hbm_bytes_per_launch")
+            traffic = json.load(open(tpath)).get("k_apply_hbm_bytes_per_step") / (n_launch // S)
         except Exception:
             traffic = None
 
@@ -194,7 +195,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_apply", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": traffic,
                      "algorithmic_bytes_per_launch": apply_bytes_per_launch,
-                     "avg_launch_ms": apply_avg_s * 1e3},
+                     "avg_launch_ms": apply_avg_s * 1e3, "launches_per_step": n_launch // S},
     }
     if breakdown:
         out["stage_ms_per_step"] = breakdown

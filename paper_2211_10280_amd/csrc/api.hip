@@ -100,6 +100,7 @@ struct tensair_model {
     u32 *keys[3], *vals[2];
     u32 *counts_out, *totals_out, *counts_in, *totals_in;
     int *seg_of, *seg_start;
+    int *long_cnt, *long_list;
     int *blk_heads, *blk_weight;
     int *pair_center;
     float *g, *center_part, *center_loss, *part_out, *part_in;
@@ -110,9 +111,9 @@ struct tensair_model {
     // second stream for the part of the gradient calculation that does not depend on the forward
     // pass (sort + segments); forked from and joined to the caller's stream with events
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    // set by tensair_step: the index of the coming apply is built on the side stream as soon as
-    // the own row ids exist, next to the forward pass and the reductions
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_index = nullptr;
+    // set by tensair_step: the index of the coming apply is built on the second stream, next to
+    // the reductions, as soon as the own row ids exist
     const ApplyArgs *fused_apply = nullptr;
     bool fused_index_done = false;
     // stage timing (tensair_profile): events recorded on the caller's stream
@@ -148,6 +149,8 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     p = take((size_t)s.nd * 4); if (m) m->totals_in = (u32 *)p;
     p = take(NE * 4); if (m) m->seg_of = (int *)p;
     p = take((NE + 2) * 4); if (m) m->seg_start = (int *)p;   // out-side rows at 0, in-side at Omax+1
+    p = take(256); if (m) m->long_cnt = (int *)p;
+    p = take((size_t)(s.tiles_out + s.tiles_in) * 4); if (m) m->long_list = (int *)p;
     p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_heads = (int *)p;
     p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_weight = (int *)p;
     p = take((size_t)s.Pmax * 4); if (m) m->pair_center = (int *)p;
@@ -311,7 +314,8 @@ int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_i
     }
     if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_index, hipEventDisableTiming) != hipSuccess) {
         tensair_model_destroy(m);
         return fail(TENSAIR_EHIP, "model_init: cannot create the side stream");
     }
@@ -385,21 +389,24 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     b.pair_base = pairs_before(center_begin, n_tokens, c.window);
     b.P = P;
 
+    // Streams.  The sort and the segment scan only need the keys, the forward pass the keys and the
+    // tables, the reductions both: the sort runs on the library's second stream next to the forward
+    // pass (fork/join by events).  Inside tensair_step the second stream then builds the index of
+    // the coming apply while the reductions run on the caller's stream.  When
+    // every stage is being timed (profile level 2) everything is serialised on the caller's stream.
+    const bool overlap = m->prof_level < 2;
+    const bool fuse = overlap && m->fused_apply != nullptr;
+    hipStream_t s_sort = overlap ? m->side : st;
     mark(m, PF_BEGIN_GRAD, st);
     // 1. keys: out-side occurrences at [0, O), in-side centers at [Omax, Omax + n_centers)
     tn_launch_build_keys(b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, epoch, m->keys[0],
                          m->keys[0] + s.Omax, m->pair_center, negatives_dbg, m->status, st);
-
     mark(m, PF_KEYS, st);
-    // The sort and the segment scan only need the keys, the forward pass only the keys and the
-    // tables: the two run side by side (second stream, fork/join by events) unless every stage
-    // is being timed, in which case they are serialised so that the stage times add up.
-    const bool overlap = m->prof_level < 2;
-    hipStream_t st2 = overlap ? m->side : st;
     if (overlap) {
         HIP_TRY(hipEventRecord(m->ev_fork, st));
         HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
     }
+
     // 2. forward on the unsorted keys (the sort never writes their buffer): g per occurrence,
     //    per-center share of the W_in gradient, loss terms
     FwdArgs f;
@@ -417,8 +424,8 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     f.inv_P = 1.0f / (float)P;
     tn_launch_forward(f, st);
     if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
-
     mark(m, PF_FORWARD, st);
+
     // 3. stable sort of both key lists by row id
     RadixProb ro, ri;
     for (int i = 0; i < 3; ++i) {
@@ -438,9 +445,9 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     ri.counts = m->counts_in;
     ri.totals = m->totals_in;
     int kb = 1;
-    const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, st2, &kb);
-
+    const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, s_sort, &kb);
     mark(m, PF_SORT, st);
+
     // 4. unique row ids, segment index per sorted entry
     SegProb so, si;
     so.keys = ro.keys[kb];
@@ -451,6 +458,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     so.blk_weight = m->blk_weight;
     so.seg_of = m->seg_of;
     so.seg_start = m->seg_start;
+    so.long_cnt = m->long_cnt;
     so.row_ids = grad_out->out.row_ids;
     so.n_rows = grad_out->out.n_rows;
     so.seg_offsets = seg_offsets_out;
@@ -464,22 +472,25 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     si.blk_weight = m->blk_weight + s.sblk_out;
     si.seg_of = m->seg_of + s.Omax;
     si.seg_start = m->seg_start + s.Omax + 1;
+    si.long_cnt = m->long_cnt + 1;
     si.row_ids = grad_out->in.row_ids;
     si.n_rows = grad_out->in.n_rows;
     si.seg_offsets = seg_offsets_in;
     si.capacity = grad_out->in.capacity;
     si.weighted = 1;
-    tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, st2);
-    if (overlap && m->fused_apply) {
-        tn_launch_apply_index(*m->fused_apply, st2);
-        m->fused_index_done = true;
-    }
+    tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, s_sort);
+    mark(m, PF_SEGMENTS, st);
     if (overlap) {
         HIP_TRY(hipEventRecord(m->ev_join, m->side));
         HIP_TRY(hipStreamWaitEvent(st, m->ev_join, 0));
     }
+    if (fuse) {   // off the critical path: the reductions run meanwhile, the apply waits for ev_index
+        tn_launch_apply_clear(*m->fused_apply, m->side);
+        tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
+        HIP_TRY(hipEventRecord(m->ev_index, m->side));
+        m->fused_index_done = true;
+    }
 
-    mark(m, PF_SEGMENTS, st);
     // 5. segmented reductions: duplicates of a row summed in sorted (= occurrence) order
     SegReduceArgs r;
     memset(&r, 0, sizeof(r));
@@ -488,6 +499,8 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.vals = si.vals;
     r.seg_of = si.seg_of;
     r.seg_start = si.seg_start;
+    r.long_cnt = si.long_cnt;
+    r.long_list = m->long_list + s.tiles_out;
     r.out_rows = grad_out->in.row_grads;
     r.part = m->part_in;
     r.mode = 1;
@@ -498,6 +511,8 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r.vals = so.vals;
     r.seg_of = so.seg_of;
     r.seg_start = so.seg_start;
+    r.long_cnt = so.long_cnt;
+    r.long_list = m->long_list;
     r.out_rows = grad_out->out.row_grads;
     r.part = m->part_out;
     r.mode = 0;
@@ -567,7 +582,8 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const 
     if (!own && n_peers == 0) return TENSAIR_OK;
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_APPLY, st);
-    tn_launch_apply_index(a, st);
+    tn_launch_apply_clear(a, st);
+    tn_launch_apply_index(a, 0, a.n_src, st);
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
     mark(m, PF_APPLY_UPDATE, st);
@@ -592,7 +608,12 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_APPLY, st);
-    if (!m->fused_index_done) tn_launch_apply_index(a, st);
+    if (m->fused_index_done) {
+        HIP_TRY(hipStreamWaitEvent(st, m->ev_index, 0));
+    } else {
+        tn_launch_apply_clear(a, st);
+        tn_launch_apply_index(a, 0, a.n_src, st);
+    }
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
     mark(m, PF_APPLY_UPDATE, st);
@@ -672,6 +693,7 @@ int tensair_model_destroy(tensair_model *m)
         for (hipEvent_t ev : m->prof_pool) (void)hipEventDestroy(ev);
         if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
         if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+        if (m->ev_index) (void)hipEventDestroy(m->ev_index);
         if (m->side) (void)hipStreamDestroy(m->side);
     }
     delete m;

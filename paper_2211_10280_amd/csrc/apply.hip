@@ -16,7 +16,11 @@
 //                  their source rows are streamed (all loads of a row issued together),
 //                  summed in source order and applied with one fused multiply-add.  A row
 //                  is written by exactly one wave: no write conflicts, fixed order of additions.
-#include <cstdlib>
+//
+// Measured and rejected: splitting the update into the rows the own gradient does not touch (which
+// could run next to the gradient calculation) and the rows it touches.  The two halves read every
+// peer block with holes, lose 20 % of the bandwidth between them, and the gradient calculation is
+// itself bound by memory traffic, so nothing was gained by the overlap.
 
 #include "dev_common.h"
 #include "kernels.h"
@@ -33,10 +37,10 @@ __global__ void __launch_bounds__(BLOCK) k_apply_clear(u64 *m0, u64 *m1, size_t 
     }
 }
 
-// grid: (blocks, n_src, 2 tables); every wave takes 64 consecutive ids of source k.
-__global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a)
+// grid: (blocks, sources, 2 tables); every wave takes 64 consecutive ids of source k0 + blockIdx.y.
+__global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 {
-    const int k = blockIdx.y, tb = blockIdx.z;
+    const int k = k0 + blockIdx.y, tb = blockIdx.z;
     const ApplySrc &s = a.src[tb][k];
     if (s.ids == nullptr) return;
     int U = *s.n_rows;
@@ -94,8 +98,46 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a)
 }
 
 // ---------------------------------------------------------------- apply
-// G  rows per wave (16, 32 or 64); NT 1: streaming (non-temporal, global) loads and stores
-template <typename T, int ITERS, int G, int NT>
+#ifndef APPLY_G
+#define APPLY_G 4   // vocabulary rows per wave (measured: 16 -> 4 rows gains 4 %)
+#endif
+
+// Sum of the sources of one row (bits of S, ascending: own first, then peers), W <- W - lr * sum.
+// lane 32*tb + k holds the position `pos` of the row in source k and that source's row pointer.
+template <typename T, int ITERS>
+__device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos, int D, int C4, int lane,
+                                           float neg_lr)
+{
+    float4 w[ITERS], acc[ITERS];
+    load_row<T, ITERS>(w, wrow, C4, lane);
+    zero_row<ITERS>(acc);
+    while (S) {
+        float4 x[4][ITERS];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (S) {
+                const int k = (int)__builtin_ctzll(S);
+                S &= S - 1ull;
+                const float *src = (const float *)rd_lane64(rows_ptr, k) + (size_t)(u32)rd_lane((int)pos, k) * D;
+                load_row<float, ITERS>(x[j], src, C4, lane);
+            } else {
+                zero_row<ITERS>(x[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) add_row<ITERS>(acc, x[j]);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        w[it].x = fmaf(neg_lr, acc[it].x, w[it].x);
+        w[it].y = fmaf(neg_lr, acc[it].y, w[it].y);
+        w[it].z = fmaf(neg_lr, acc[it].z, w[it].z);
+        w[it].w = fmaf(neg_lr, acc[it].w, w[it].w);
+    }
+    store_row<T, ITERS>(wrow, w, C4, lane);
+}
+
+template <typename T, int ITERS, int G>
 __global__ void __launch_bounds__(BLOCK) k_apply(ApplyArgs a, int nblocks)
 {
     // keep runs of APPLY_CHUNK consecutive workgroups on one XCD (workgroups are dealt
@@ -163,251 +205,52 @@ __global__ void __launch_bounds__(BLOCK) k_apply(ApplyArgs a, int nblocks)
             // per lane: position of row r in its source (if present and in bounds)
             const u32 pos = st + (u32)__popcll(m & ((1ull << b) - 1ull));
             const bool ok = mine && ((m >> b) & 1ull) && (pos < (u32)U);
-            u64 S = __ballot(ok);   // bit 32*tb + k: source k has row r
-            T *wrow = table + (size_t)r * a.stride;
-            float4 w[ITERS], acc[ITERS];
-            if (NT == 2) zero_row<ITERS>(w);
-            else if (NT == 1) load_row_s<T, ITERS>(w, wrow, C4, lane);
-            else load_row<T, ITERS>(w, wrow, C4, lane);
-            zero_row<ITERS>(acc);
-            if (NT == 3) S = 0;
-            while (S) {
-                float4 x[4][ITERS];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (S) {
-                        const int k = (int)__builtin_ctzll(S);   // ascending: own first, then peers
-                        S &= S - 1ull;
-                        const float *src = (const float *)rd_lane64(rows_ptr, k) +
-                                           (size_t)(u32)rd_lane((int)pos, k) * a.D;
-                        if (NT) load_row_s<float, ITERS>(x[j], src, C4, lane);
-                        else load_row<float, ITERS>(x[j], src, C4, lane);
-                    } else {
-                        zero_row<ITERS>(x[j]);
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) add_row<ITERS>(acc, x[j]);
-            }
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                w[it].x = fmaf(neg_lr, acc[it].x, w[it].x);
-                w[it].y = fmaf(neg_lr, acc[it].y, w[it].y);
-                w[it].z = fmaf(neg_lr, acc[it].z, w[it].z);
-                w[it].w = fmaf(neg_lr, acc[it].w, w[it].w);
-            }
-            if (NT == 2) { if (w[0].x == 1234.5678f) store_row<T, ITERS>(wrow, w, C4, lane); }
-            else if (NT == 1) store_row_s<T, ITERS>(wrow, w, C4, lane);
-            else store_row<T, ITERS>(wrow, w, C4, lane);
+            const u64 S = __ballot(ok);   // bit 32*tb + k: source k has row r
+            update_row<T, ITERS>(table + (size_t)r * a.stride, S, rows_ptr, pos, a.D, C4, lane, neg_lr);
         }
     }
 }
 
-// Persistent form: a fixed number of resident waves stride over the groups of G rows, so that at
-// any moment the rows in flight across the chip are neighbours in memory (a narrow front through
-// the tables and through every gradient block, which is what keeps HBM pages open); the
-// (start, mask) words of the next group are fetched while the current rows are processed.
-template <typename T, int ITERS, int G>
-__global__ void __launch_bounds__(BLOCK) k_apply_persist(ApplyArgs a, int ngroups)
-{
-    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
-    const int nblocks = gridDim.x;
-    const int nwaves = nblocks * WAVES_PER_BLOCK;
-    // workgroups are dealt round-robin to the 8 XCDs: give every XCD a contiguous share of each
-    // front, so rows that share a cache line meet in the same L2
-    int gw;
-    {
-        const int b = blockIdx.x;
-        const int per = nblocks >> 3;
-        if ((nblocks & 7) == 0) gw = ((b & 7) * per + (b >> 3)) * WAVES_PER_BLOCK + wave;
-        else gw = b * WAVES_PER_BLOCK + wave;
-    }
-    const int ns = a.n_src;
-    const int C4 = a.D >> 2;
-    const int tb_l = lane >> 5, k_l = lane & 31;
-    bool have = false;
-    int U = 0;
-    u64 rows_ptr = 0;
-    const u64 *mask_l = a.mask[tb_l];
-    const u32 *start_l = a.start[tb_l];
-    if (k_l < ns) {
-        const ApplySrc &s = a.src[tb_l][k_l];
-        if (s.ids != nullptr) {
-            have = true;
-            U = *s.n_rows;
-            if ((i64)U > s.capacity) U = (int)s.capacity;
-            rows_ptr = (u64)s.rows;
-        }
-    }
-    const float neg_lr = -a.lr;
-    constexpr int GPW = 64 / G;
-    u64 mk_n = 0;
-    u32 st_n = 0;
-    if (have && gw < ngroups) {
-        const size_t at = (size_t)(gw / GPW) * ns + k_l;
-        mk_n = mask_l[at];
-        st_n = start_l[at];
-    }
-    for (int g = gw; g < ngroups; g += nwaves) {
-        const u64 mk = mk_n;
-        u32 st = st_n;
-        const int gn = g + nwaves;
-        if (have && gn < ngroups) {
-            const size_t at = (size_t)(gn / GPW) * ns + k_l;
-            mk_n = mask_l[at];
-            st_n = start_l[at];
-        }
-        const int word = g / GPW, lo = (g - word * GPW) * G;
-        st += (u32)__popcll(mk & ((1ull << lo) - 1ull));
-        const u64 m = (G == 64) ? mk : ((mk >> lo) & ((1ull << (G & 63)) - 1ull));
-        const i64 row0 = (i64)word * 64 + lo;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            const bool mine = tb_l == tb;
-            u64 um;
-            {
-                u32 lo32 = (u32)uniform((int)wave_or(mine ? (u32)m : 0u));
-                u32 hi32 = (G > 32) ? (u32)uniform((int)wave_or(mine ? (u32)(m >> 32) : 0u)) : 0u;
-                um = ((u64)hi32 << 32) | lo32;
-            }
-            T *table = (T *)a.table[tb];
-            while (um) {
-                const int b = (int)__builtin_ctzll(um);
-                um &= um - 1ull;
-                const i64 r = row0 + b;
-                if (r >= a.V) break;   // only reachable with a corrupt index (flagged input)
-                const u32 pos = st + (u32)__popcll(m & ((1ull << b) - 1ull));
-                const bool ok = mine && ((m >> b) & 1ull) && (pos < (u32)U);
-                u64 S = __ballot(ok);
-                T *wrow = table + (size_t)r * a.stride;
-                float4 w[ITERS], acc[ITERS];
-                load_row<T, ITERS>(w, wrow, C4, lane);
-                zero_row<ITERS>(acc);
-                while (S) {
-                    float4 x[4][ITERS];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (S) {
-                            const int k = (int)__builtin_ctzll(S);   // ascending: own first, then peers
-                            S &= S - 1ull;
-                            const float *src = (const float *)rd_lane64(rows_ptr, k) +
-                                               (size_t)(u32)rd_lane((int)pos, k) * a.D;
-                            load_row<float, ITERS>(x[j], src, C4, lane);
-                        } else {
-                            zero_row<ITERS>(x[j]);
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) add_row<ITERS>(acc, x[j]);
-                }
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    w[it].x = fmaf(neg_lr, acc[it].x, w[it].x);
-                    w[it].y = fmaf(neg_lr, acc[it].y, w[it].y);
-                    w[it].z = fmaf(neg_lr, acc[it].z, w[it].z);
-                    w[it].w = fmaf(neg_lr, acc[it].w, w[it].w);
-                }
-                store_row<T, ITERS>(wrow, w, C4, lane);
-            }
-        }
-    }
-}
-
-template <typename T, int ITERS, int G>
-static void launch_apply_persist_i(const ApplyArgs &a, hipStream_t st)
-{
-    static int blocks_per_cu = 0, cus = 0;
-    if (blocks_per_cu == 0) {
-        int dev = 0;
-        (void)hipGetDevice(&dev);
-        hipDeviceProp_t prop;
-        (void)hipGetDeviceProperties(&prop, dev);
-        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_apply_persist<T, ITERS, G>, BLOCK, 0) != hipSuccess || occ < 1)
-            occ = 4;
-        blocks_per_cu = occ;
-    }
-    const int words = (int)((a.V + 63) >> 6);
-    const i64 ngroups = (i64)words * (64 / G);
-    int mult = 1;
-    if (const char *e = getenv("TENSAIR_APPLY_OCC")) mult = atoi(e);
-    i64 nblocks = (i64)cus * (mult > 0 ? (blocks_per_cu < mult ? blocks_per_cu : mult) : blocks_per_cu);
-    const i64 need = (ngroups + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    if (nblocks > need) nblocks = need;
-    hipLaunchKernelGGL((k_apply_persist<T, ITERS, G>), dim3((unsigned)nblocks), dim3(BLOCK), 0, st, a, (int)ngroups);
-}
-
-template <typename T, int G>
-static void launch_apply_persist_t(const ApplyArgs &a, hipStream_t st)
-{
-    const int iters = (a.D / 4 + WAVE - 1) / WAVE;
-    switch (iters) {
-    case 1: launch_apply_persist_i<T, 1, G>(a, st); break;
-    case 2: launch_apply_persist_i<T, 2, G>(a, st); break;
-    case 3: launch_apply_persist_i<T, 3, G>(a, st); break;
-    default: launch_apply_persist_i<T, 4, G>(a, st); break;
-    }
-}
-
-template <typename T, int G, int NT>
+template <typename T>
 static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
 {
-    const int words = (int)((a.V + 63) >> 6);
-    const i64 nwaves = (i64)words * (64 / G);
-    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
+    const int words = (int)((a.V + 63) >> 6);
+    const i64 nwaves = (i64)words * (64 / APPLY_G);
+    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     dim3 grid(nblocks), blk(BLOCK);
     switch (iters) {
-    case 1: hipLaunchKernelGGL((k_apply<T, 1, G, NT>), grid, blk, 0, st, a, nblocks); break;
-    case 2: hipLaunchKernelGGL((k_apply<T, 2, G, NT>), grid, blk, 0, st, a, nblocks); break;
-    case 3: hipLaunchKernelGGL((k_apply<T, 3, G, NT>), grid, blk, 0, st, a, nblocks); break;
-    default: hipLaunchKernelGGL((k_apply<T, 4, G, NT>), grid, blk, 0, st, a, nblocks); break;
+    case 1: hipLaunchKernelGGL((k_apply<T, 1, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
+    case 2: hipLaunchKernelGGL((k_apply<T, 2, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
+    case 3: hipLaunchKernelGGL((k_apply<T, 3, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
+    default: hipLaunchKernelGGL((k_apply<T, 4, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
     }
 }
 
-void tn_launch_apply_index(const ApplyArgs &a, hipStream_t st)
+void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st)
 {
     const size_t words = (size_t)((a.V + 63) >> 6);
     const size_t n = words * (size_t)a.n_src;
     hipLaunchKernelGGL(k_apply_clear, dim3((unsigned)((n + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, st,
                        a.mask[0], a.mask[1], n);
+}
+
+// index of the sources k_begin .. k_end-1 (the masks must have been cleared)
+void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st)
+{
+    if (k_end <= k_begin) return;
     // enough waves to cover the largest possible id list, grid-strided
     i64 maxcap = 1;
     for (int tb = 0; tb < 2; ++tb)
-        for (int k = 0; k < a.n_src; ++k)
+        for (int k = k_begin; k < k_end; ++k)
             if (a.src[tb][k].ids && a.src[tb][k].capacity > maxcap) maxcap = a.src[tb][k].capacity;
     i64 want = (maxcap + BLOCK - 1) / BLOCK;
     int blocks = (int)(want > 2048 ? 2048 : want);
-    hipLaunchKernelGGL(k_apply_index, dim3(blocks, a.n_src, 2), dim3(BLOCK), 0, st, a);
+    hipLaunchKernelGGL(k_apply_index, dim3(blocks, k_end - k_begin, 2), dim3(BLOCK), 0, st, a, k_begin);
 }
 
 void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st)
 {
-    static int variant = -1;
-    if (variant < 0) {
-        const char *e = getenv("TENSAIR_APPLY_VARIANT");
-        variant = e ? atoi(e) : 0;
-    }
-    const int g = variant / 10, nt = variant % 10;
-    if (a.dtype == 0) {
-        if (g == 0 && nt == 2) launch_apply_t<float, 16, 2>(a, st);
-        else if (g == 0 && nt == 3) launch_apply_t<float, 16, 3>(a, st);
-        else if (g == 0 && nt == 0) launch_apply_t<float, 16, 0>(a, st);
-        else if (g == 0) launch_apply_t<float, 16, 1>(a, st);
-        else if (g == 1 && nt == 0) launch_apply_t<float, 32, 0>(a, st);
-        else if (g == 1) launch_apply_t<float, 32, 1>(a, st);
-        else if (g == 2 && nt == 0) launch_apply_t<float, 64, 0>(a, st);
-        else if (g == 2) launch_apply_t<float, 64, 1>(a, st);
-        else if (g == 3) launch_apply_t<float, 8, 0>(a, st);
-        else if (g == 4) launch_apply_t<float, 4, 0>(a, st);
-        else if (g == 5) launch_apply_t<float, 2, 0>(a, st);
-        else if (g == 6) launch_apply_t<float, 1, 0>(a, st);
-        else if (g == 7) launch_apply_persist_t<float, 1>(a, st);
-        else if (g == 8) launch_apply_persist_t<float, 2>(a, st);
-        else if (g == 9) launch_apply_persist_t<float, 4>(a, st);
-        else launch_apply_persist_t<float, 8>(a, st);
-    } else {
-        launch_apply_t<bf16_t, 16, 0>(a, st);
-    }
+    if (a.dtype == 0) launch_apply_t<float>(a, st);
+    else launch_apply_t<bf16_t>(a, st);
 }

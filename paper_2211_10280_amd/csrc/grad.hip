@@ -263,47 +263,38 @@ __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
     }
     float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
     store_row<float, ITERS>(dst, acc, C4, lane);
+    // a long row begins in this tile: leave its tile for the kernel that chains the partials
+    // (integer counter; the order of the list does not matter, every chain is independent)
+    if (dest == 2 && lane == 0) a.long_list[atomicAdd(a.long_cnt, 1)] = tile;
 }
 
-// Chains the partials of long rows in tile order.  One wave looks at one tile: if the tile's last
-// row is long and begins in this tile, the workgroup sums part[tile][1] and the leading partials
-// part[t][0] of the following tiles the row covers, four waves sharing the chain.
+// Chains the partials of long rows in tile order: one workgroup per long row (grid-strided
+// over the list the reduction left), its waves sharing the chain part[tile][1], part[tile+1][0], ...
 template <int ITERS, int TILE>
-__global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
+// (512-thread workgroups: 1024-thread ones wait for a whole compute unit's worth of free wave
+// slots when another kernel fills the chip, which starved this kernel for hundreds of microseconds)
+#define FIXUP_THREADS 512
+__global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReduceArgs a)
 {
-    __shared__ float red[WAVES_PER_BLOCK][ITERS * WAVE * 4];
-    __shared__ int s_row[WAVES_PER_BLOCK], s_len[WAVES_PER_BLOCK];
+    constexpr int NW = FIXUP_THREADS / WAVE;
+    __shared__ float red[NW][ITERS * WAVE * 4];
     const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int C4 = a.D >> 2;
-    {
-        const int tile = blockIdx.x * WAVES_PER_BLOCK + wave;
-        const int t0 = tile * TILE;
-        int row = -1, len = 0;
-        if (t0 < a.n) {
-            const int t1 = min(a.n, t0 + TILE);
-            const int r = a.seg_of[t1 - 1];
-            const int start = a.seg_start[r], end = a.seg_start[r + 1];
-            if (start >= t0 && (end - start) > TILE) {
-                row = r;
-                len = (end - 1) / TILE - tile;   // tiles after this one that hold a leading partial
-            }
-        }
-        if (lane == 0) { s_row[wave] = row; s_len[wave] = len; }
-    }
-    __syncthreads();
-    for (int q = 0; q < WAVES_PER_BLOCK; ++q) {
-        const int row = s_row[q];
-        if (row < 0) continue;                       // uniform over the workgroup
-        const int tile = blockIdx.x * WAVES_PER_BLOCK + q;
-        const int len = s_len[q];
+    const int count = *a.long_cnt;
+    for (int i = blockIdx.x; i < count; i += gridDim.x) {
+        const int tile = a.long_list[i];
+        const int t1 = min(a.n, tile * TILE + TILE);
+        const int row = a.seg_of[t1 - 1];
+        const int end = a.seg_start[row + 1];
+        const int len = (end - 1) / TILE - tile;   // tiles after this one that hold a leading partial
         float4 acc[ITERS];
         zero_row<ITERS>(acc);
         if (wave == 0) load_row<float, ITERS>(acc, a.part + ((size_t)tile * 2 + 1) * a.D, C4, lane);
-        for (int j0 = wave; j0 < len; j0 += WAVES_PER_BLOCK * SEG_UNROLL) {
+        for (int j0 = wave; j0 < len; j0 += NW * SEG_UNROLL) {
             float4 r[SEG_UNROLL][ITERS];
 #pragma unroll
             for (int x = 0; x < SEG_UNROLL; ++x) {
-                int j = j0 + x * WAVES_PER_BLOCK;
+                int j = j0 + x * NW;
                 if (j < len) load_row<float, ITERS>(r[x], a.part + (size_t)(tile + 1 + j) * 2 * a.D, C4, lane);
                 else zero_row<ITERS>(r[x]);
             }
@@ -320,10 +311,10 @@ __global__ void __launch_bounds__(BLOCK) k_segfixup(SegReduceArgs a)
         }
         __syncthreads();
         float *dst = a.out_rows + (size_t)row * a.D;
-        for (int e = threadIdx.x; e < a.D; e += BLOCK) {
+        for (int e = threadIdx.x; e < a.D; e += FIXUP_THREADS) {
             float s = red[0][e];
 #pragma unroll
-            for (int w = 1; w < WAVES_PER_BLOCK; ++w) s += red[w][e];
+            for (int w = 1; w < NW; ++w) s += red[w][e];
             dst[e] = s;
         }
         __syncthreads();
@@ -336,7 +327,10 @@ static void launch_segreduce_i(const SegReduceArgs &a, hipStream_t st)
     int ntiles = (a.n + TILE - 1) / TILE;
     dim3 grid((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), blk(BLOCK);
     hipLaunchKernelGGL((k_segreduce<T, ITERS, MODE, TILE>), grid, blk, 0, st, a);
-    if (ntiles > 1) hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), grid, blk, 0, st, a);
+    if (ntiles > 1) {
+        int fb = ntiles < 1024 ? ntiles : 1024;
+        hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), dim3(fb), dim3(FIXUP_THREADS), 0, st, a);
+    }
 }
 
 template <typename T, int MODE>

@@ -56,6 +56,7 @@ struct SegProb {
     int *blk_weight;      // [nblk] scratch
     int *seg_of;          // [n] out: row index (0..U-1) of every sorted entry
     int *seg_start;       // [U+1] out: index of the first sorted entry of every row, then n
+    int *long_cnt;        // [1] zeroed here: the segmented reduction counts its long rows in it
     int *row_ids;         // [capacity] out
     int *n_rows;          // [1] out
     int *seg_offsets;     // [U+1] out or NULL
@@ -86,6 +87,8 @@ struct SegReduceArgs {
     const int *seg_start;  // first sorted entry of every row; [U] = n
     float *out_rows;       // [U][D]
     float *part;           // [ntiles][2][D] scratch for rows that cross tile borders
+    int *long_cnt;         // [1] number of long rows found (zeroed by the segment scan)
+    int *long_list;        // [ntiles] tiles in which a long row begins, in no particular order
     int D;
     // source of the contribution of an entry:
     //  mode 0 (out-side): value = occurrence index o; row = g[o] * W_in[pair_center[o/(N+1)]]
@@ -123,7 +126,8 @@ struct ApplyArgs {
     float lr;
     int *status;
 };
-void tn_launch_apply_index(const ApplyArgs &a, hipStream_t st);
+void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st);
+void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st);
 void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st);
 
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)

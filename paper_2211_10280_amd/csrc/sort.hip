@@ -276,6 +276,7 @@ __global__ void __launch_bounds__(BLOCK) k_seg_assign(SegPass a)
     int b = blockIdx.x, pr = 0;
     if (b >= a.p[0].nblk) { b -= a.p[0].nblk; pr = 1; }
     const SegProb &p = a.p[pr];
+    if (b == 0 && threadIdx.x == 0) *p.long_cnt = 0;
     // heads / weight of all earlier blocks
     int ph = 0, pw = 0;
     for (int j = threadIdx.x; j < b; j += BLOCK) { ph += p.blk_heads[j]; pw += p.blk_weight[j]; }
