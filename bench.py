@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 1M-vocab configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefetch", action="store_true",
+                    help="every step self-contained (default: the next mini-batch is handed to tensair_prefetch "
+                         "after each step, as it would be waiting in the worker's input queue)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -70,7 +73,7 @@ def main():
     tok, counts = W.make_stream(cfg)
     log(f"[bench] workload {cfg.name}: stream of {cfg.tokens} tokens in {time.perf_counter() - t0:.1f}s")
 
-    worker = DasgdWorker(cfg, tok, counts)
+    worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch)
     model = worker.model
     theta0 = (model.w_in.clone(), model.w_out.clone())
     D, e = cfg.dim, cfg.elem_bytes
@@ -105,7 +108,7 @@ def main():
 
     def reset():
         model.w_in.copy_(theta0[0]); model.w_out.copy_(theta0[1])
-        worker.step_no = 0
+        worker.restart()
 
     # ---- replay: warmup, then the timed region
     reset()
@@ -188,7 +191,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "vocab": cfg.vocab, "dim": cfg.dim, "window": cfg.window,
                    "negatives": cfg.negatives, "batch_centers": cfg.batch, "peers": K,
-                   "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S},
+                   "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S,
+                   "next_batch_prefetch": not args.no_prefetch},
         "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
         "measured_copy_GBps": copy_GBps,
         "step_algorithmic_bytes": step_bytes / S,

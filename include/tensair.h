@@ -7,14 +7,17 @@
  *   calculate_gradient(model, minibatch) -> tensair_sgns_grad      (gradient calculation, Section 2.2)
  *   apply_gradient(model, gradient)      -> tensair_dasgd_apply    (gradient application, Eq. 1)
  *   train(minibatch) incl. peer messages -> tensair_step
+ *   a mini-batch waiting in the operator's input queue -> tensair_prefetch (optional)
  *
  * Conventions for every call
  *   - Plain C ABI.  Pointers marked DEVICE point to GPU memory owned by the caller;
  *     pointers marked HOST point to host memory.  The library allocates no device
  *     memory: everything it needs lives in the caller's workspace.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All GPU
- *     work is enqueued on it; no call waits for the GPU except tensair_status and
- *     tensair_model_init (which uploads the alias table).  Sizes that depend on the data
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The results
+ *     of every call are complete on it (the library forks part of the work to a stream of
+ *     its own and joins it again); use one stream for all calls on a model.  No call waits
+ *     for the GPU except tensair_status, tensair_model_destroy and tensair_model_init
+ *     (which uploads the alias table).  Sizes that depend on the data
  *     (number of unique rows) stay on the device.
  *   - Return value: TENSAIR_OK or a negative tensair_status code; host-detectable
  *     argument errors are reported before anything is launched;
@@ -152,6 +155,26 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
                  int32_t n_peers, float lr, tensair_sparse_grad *own_out, float *mean_loss,
                  void *stream);
 
+/* Announces a coming mini-batch, so that the part of its tensair_sgns_grad / tensair_step
+ * call that does not depend on the tables -- pair enumeration, negatives, sort by row id,
+ * segments, unique row ids -- is prepared ahead of time on the library's own stream, next to
+ * whatever the caller's stream is doing (in TensAIR's dataflow, Section 3, mini-batches queue
+ * up at the Model operator: the coming ones are known while the current one trains).
+ * Up to two announcements are kept, in order: the first is prepared at once; a second one is
+ * prepared at the start of the gradient call that consumes the first (next to that call's
+ * forward pass), a third replaces the second.  A gradient call on this model uses the
+ * prepared data if its (tokens, n_tokens, center_begin, n_centers, epoch) and the model's
+ * worker id are those of the oldest announcement -- its results are then bit-identical to
+ * those of a call without prefetch -- and otherwise drops every announcement.
+ * A mini-batch without pairs is not recorded.
+ * Ordering: the preparation may start as soon as everything enqueued on `stream` before
+ * the START of the most recent gradient call on this model has finished (before this call,
+ * if the library's stream has not followed that call), so the token range must be ready by
+ * then and must stay unchanged until the consuming call has run.
+ * Same argument checks and error codes as tensair_sgns_grad. */
+int tensair_prefetch(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                     int32_t n_centers, uint32_t epoch, void *stream);
+
 /* Waits for `stream`, then returns TENSAIR_OK, TENSAIR_EDATA (and clears the device
  * status word) or TENSAIR_EHIP. */
 int tensair_status(tensair_model *m, void *stream);
@@ -172,6 +195,7 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
  * streaming-bandwidth ceiling of the box and the calibration of its HBM byte counters. */
 int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
 
+/* Waits for the library's own stream (a pending prefetch), then frees the host handle. */
 int tensair_model_destroy(tensair_model *m);
 
 const char *tensair_last_error(void);

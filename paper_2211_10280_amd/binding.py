@@ -25,6 +25,7 @@ SYMBOLS = [
     "tensair_model_rebind", "tensair_model_alias", "tensair_pair_count", "tensair_sgns_grad",
     "tensair_dasgd_apply", "tensair_step", "tensair_status", "tensair_model_destroy",
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
+    "tensair_prefetch",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -89,6 +90,8 @@ def lib():
         L.tensair_step.argtypes = [vp, vp, i64, i64, i32, u32, C.POINTER(SparseGrad), i32, C.c_float,
                                    C.POINTER(SparseGrad), vp, vp]
         L.tensair_step.restype = C.c_int
+        L.tensair_prefetch.argtypes = [vp, vp, i64, i64, i32, u32, vp]
+        L.tensair_prefetch.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
@@ -232,6 +235,11 @@ def tensair_step(h, tokens, center_begin: int, n_centers: int, epoch: int, peers
                               _stream(stream)))
 
 
+def tensair_prefetch(h, tokens, center_begin: int, n_centers: int, epoch: int, stream=None):
+    _check(lib().tensair_prefetch(h, _ptr(tokens), tokens.numel(), center_begin, n_centers, epoch,
+                                  _stream(stream)))
+
+
 def tensair_status(h, stream=None):
     _check(lib().tensair_status(h, _stream(stream)))
 
@@ -302,6 +310,9 @@ class Model:
 
     def step(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
         tensair_step(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+
+    def prefetch(self, tokens, begin, n, epoch):
+        tensair_prefetch(self.h, tokens, begin, n, epoch)
 
     def status(self):
         tensair_status(self.h)

@@ -89,6 +89,35 @@ Sizes sizes_of(const tensair_config &c)
 
 }  // namespace
 
+// Everything about a mini-batch that does not depend on the tables: keys (pairs and negatives), their
+// sorted order, segments, unique row ids.  There are two sets, used in turn, so that the set of the
+// coming mini-batch can be filled (tensair_prefetch) while the kernels of the current one still read theirs.
+struct BatchSet {
+    u32 *keys[3], *vals[2];
+    u32 *counts_out, *totals_out, *counts_in, *totals_in;
+    int *seg_of, *seg_start;
+    int *long_cnt;
+    int *blk_heads, *blk_weight;
+    int *pair_center;
+    // row index of a prefetched mini-batch, copied to the caller's buffers when it is consumed
+    int *ids_in, *ids_out, *n_rows, *off_in, *off_out;
+    int cur = 0, kb = 1;   // which vals / keys buffer holds the sorted order
+};
+
+// A mini-batch announced by tensair_prefetch.
+struct Prefetched {
+    bool valid = false;
+    const int32_t *tokens = nullptr;
+    i64 n_tokens = 0, begin = 0, P = 0;
+    int n_centers = 0;
+    u32 epoch = 0, worker_id = 0;
+    bool is(const int32_t *t, i64 nt, i64 b, int n, u32 e, u32 w) const
+    {
+        return valid && tokens == t && n_tokens == nt && begin == b && n_centers == n && epoch == e &&
+               worker_id == w;
+    }
+};
+
 struct tensair_model {
     tensair_config cfg;
     Sizes sz;
@@ -97,12 +126,8 @@ struct tensair_model {
     u32 *thr;
     int *alias;
     int *status;
-    u32 *keys[3], *vals[2];
-    u32 *counts_out, *totals_out, *counts_in, *totals_in;
-    int *seg_of, *seg_start;
-    int *long_cnt, *long_list;
-    int *blk_heads, *blk_weight;
-    int *pair_center;
+    BatchSet set[2];
+    int *long_list;
     float *g, *center_part, *center_loss, *part_out, *part_in;
     u32 *start[2];
     u64 *mask[2];
@@ -111,11 +136,22 @@ struct tensair_model {
     // second stream for the part of the gradient calculation that does not depend on the forward
     // pass (sort + segments); forked from and joined to the caller's stream with events
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_index = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_fwd = nullptr, ev_segs = nullptr, ev_index = nullptr;
+    // mini-batch sets: `busy` is the one the most recent gradient call reads; announced mini-batches are
+    // prepared into the other one on the second stream (ev_prep recorded behind them)
+    int busy = 1;
+    Prefetched pend;               // prepared (or being prepared) in set 1 - busy
+    Prefetched next;               // announced after `pend`: prepared when `pend` is consumed
+    hipEvent_t ev_prep = nullptr, ev_reduced = nullptr;
+    bool side_follows = false;     // the second stream has waited for the start of the latest gradient call
+    // every event recorded on the second stream takes a ticket; the caller's stream is behind all of
+    // them up to main_ticket, so a prepared set with prep_ticket <= main_ticket needs no wait
+    u64 side_ticket = 0, main_ticket = 0, prep_ticket = 0, index_ticket = 0;
     // set by tensair_step: the index of the coming apply is built on the second stream, next to
     // the reductions, as soon as the own row ids exist
     const ApplyArgs *fused_apply = nullptr;
     bool fused_index_done = false;
+    bool prepare_under_apply = false;   // tensair_step: the table update is long enough to hide a preparation
     // stage timing (tensair_profile): events recorded on the caller's stream
     int prof_level = 0;
     std::vector<hipEvent_t> prof_pool;
@@ -141,19 +177,29 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     p = take(V * 4); if (m) m->thr = (u32 *)p;
     p = take(V * 4); if (m) m->alias = (int *)p;
     p = take(256); if (m) m->status = (int *)p;
-    for (int i = 0; i < 3; ++i) { p = take(NE * 4); if (m) m->keys[i] = (u32 *)p; }
-    for (int i = 0; i < 2; ++i) { p = take(NE * 4); if (m) m->vals[i] = (u32 *)p; }
-    p = take((size_t)s.nd * s.nblk_out * 4); if (m) m->counts_out = (u32 *)p;
-    p = take((size_t)s.nd * 4); if (m) m->totals_out = (u32 *)p;
-    p = take((size_t)s.nd * s.nblk_in * 4); if (m) m->counts_in = (u32 *)p;
-    p = take((size_t)s.nd * 4); if (m) m->totals_in = (u32 *)p;
-    p = take(NE * 4); if (m) m->seg_of = (int *)p;
-    p = take((NE + 2) * 4); if (m) m->seg_start = (int *)p;   // out-side rows at 0, in-side at Omax+1
-    p = take(256); if (m) m->long_cnt = (int *)p;
+    const size_t cap_in = (size_t)(s.Bmax < (i64)V ? s.Bmax : (i64)V);
+    const size_t cap_out = (size_t)(s.Omax < (i64)V ? s.Omax : (i64)V);
+    for (int u = 0; u < 2; ++u) {
+        BatchSet *b = m ? &m->set[u] : nullptr;
+        for (int i = 0; i < 3; ++i) { p = take(NE * 4); if (b) b->keys[i] = (u32 *)p; }
+        for (int i = 0; i < 2; ++i) { p = take(NE * 4); if (b) b->vals[i] = (u32 *)p; }
+        p = take((size_t)s.nd * s.nblk_out * 4); if (b) b->counts_out = (u32 *)p;
+        p = take((size_t)s.nd * 4); if (b) b->totals_out = (u32 *)p;
+        p = take((size_t)s.nd * s.nblk_in * 4); if (b) b->counts_in = (u32 *)p;
+        p = take((size_t)s.nd * 4); if (b) b->totals_in = (u32 *)p;
+        p = take(NE * 4); if (b) b->seg_of = (int *)p;
+        p = take((NE + 2) * 4); if (b) b->seg_start = (int *)p;   // out-side rows at 0, in-side at Omax+1
+        p = take(256); if (b) b->long_cnt = (int *)p;
+        p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (b) b->blk_heads = (int *)p;
+        p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (b) b->blk_weight = (int *)p;
+        p = take((size_t)s.Pmax * 4); if (b) b->pair_center = (int *)p;
+        p = take(cap_in * 4); if (b) b->ids_in = (int *)p;
+        p = take(cap_out * 4); if (b) b->ids_out = (int *)p;
+        p = take(256); if (b) b->n_rows = (int *)p;
+        p = take((cap_in + 1) * 4); if (b) b->off_in = (int *)p;
+        p = take((cap_out + 1) * 4); if (b) b->off_out = (int *)p;
+    }
     p = take((size_t)(s.tiles_out + s.tiles_in) * 4); if (m) m->long_list = (int *)p;
-    p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_heads = (int *)p;
-    p = take((size_t)(s.sblk_out + s.sblk_in) * 4); if (m) m->blk_weight = (int *)p;
-    p = take((size_t)s.Pmax * 4); if (m) m->pair_center = (int *)p;
     p = take((size_t)s.Omax * 4); if (m) m->g = (float *)p;
     p = take((size_t)s.Bmax * D * 4); if (m) m->center_part = (float *)p;
     p = take((size_t)s.Bmax * 4); if (m) m->center_loss = (float *)p;
@@ -314,8 +360,11 @@ int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_i
     }
     if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&m->ev_index, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&m->ev_fwd, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_segs, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_index, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_prep, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_reduced, hipEventDisableTiming) != hipSuccess) {
         tensair_model_destroy(m);
         return fail(TENSAIR_EHIP, "model_init: cannot create the side stream");
     }
@@ -351,19 +400,175 @@ int64_t tensair_pair_count(const tensair_model *m, int64_t n_tokens, int64_t cen
     return pair_count(m->cfg, n_tokens, center_begin, n_centers);
 }
 
+// The table-independent part of a mini-batch, split in two so that other work can be enqueued in
+// between: keys (pairs, negatives), then sort + segments.
+struct BatchWork {
+    BatchDesc b;
+    i64 P, O;
+    u32 epoch;
+};
+
+static BatchWork batch_work(const tensair_config &c, const int32_t *tokens, i64 n_tokens, i64 center_begin,
+                            int n_centers, u32 epoch, i64 P)
+{
+    BatchWork w;
+    w.b.tok = tokens;
+    w.b.T = n_tokens;
+    w.b.begin = center_begin;
+    w.b.n_centers = n_centers;
+    w.b.w = c.window;
+    w.b.N = c.negatives;
+    w.b.pair_base = pairs_before(center_begin, n_tokens, c.window);
+    w.b.P = P;
+    w.P = P;
+    w.O = P * (c.negatives + 1);
+    w.epoch = epoch;
+    return w;
+}
+
+// keys: out-side occurrences at [0, O), in-side centers at [Omax, Omax + n_centers)
+static void enqueue_keys(tensair_model *m, BatchSet &S, const BatchWork &w, int32_t *negatives_dbg, hipStream_t st)
+{
+    const tensair_config &c = m->cfg;
+    tn_launch_build_keys(w.b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, w.epoch, S.keys[0],
+                         S.keys[0] + m->sz.Omax, S.pair_center, negatives_dbg, m->status, st);
+}
+
+struct RowIndexDst {
+    int *ids, *n_rows, *offsets;
+    i64 capacity;
+};
+
+static SegProb seg_prob(const tensair_model *m, const BatchSet &S, int side, int n)
+{
+    const Sizes &s = m->sz;
+    SegProb p;
+    memset(&p, 0, sizeof(p));
+    const size_t at = side ? (size_t)s.Omax : 0;
+    p.keys = S.keys[S.kb] + at;
+    p.vals = S.vals[S.cur] + at;
+    p.n = n;
+    p.nblk = (n + TN_SCAN_TILE - 1) / TN_SCAN_TILE;
+    p.blk_heads = S.blk_heads + (side ? s.sblk_out : 0);
+    p.blk_weight = S.blk_weight + (side ? s.sblk_out : 0);
+    p.seg_of = S.seg_of + at;
+    p.seg_start = S.seg_start + (side ? (size_t)s.Omax + 1 : 0);
+    p.long_cnt = S.long_cnt + side;
+    p.weighted = side;
+    return p;
+}
+
+// stable sort of both key lists by row id, then unique row ids and the segment of every sorted entry
+static void enqueue_sort_segments(tensair_model *m, BatchSet &S, const BatchWork &w, const RowIndexDst &in,
+                                  const RowIndexDst &out, hipStream_t st, hipStream_t st_mark)
+{
+    const tensair_config &c = m->cfg;
+    const Sizes &s = m->sz;
+    RadixProb ro, ri;
+    for (int i = 0; i < 3; ++i) {
+        ro.keys[i] = S.keys[i];
+        ri.keys[i] = S.keys[i] + s.Omax;
+    }
+    for (int i = 0; i < 2; ++i) {
+        ro.vals[i] = S.vals[i];
+        ri.vals[i] = S.vals[i] + s.Omax;
+    }
+    ro.n = (int)w.O;
+    ro.nblk = (int)((w.O + TN_RADIX_TILE - 1) / TN_RADIX_TILE);
+    ro.counts = S.counts_out;
+    ro.totals = S.totals_out;
+    ri.n = w.b.n_centers;
+    ri.nblk = (w.b.n_centers + TN_RADIX_TILE - 1) / TN_RADIX_TILE;
+    ri.counts = S.counts_in;
+    ri.totals = S.totals_in;
+    S.cur = tn_launch_radix_sort(ro, ri, s.key_bits, st, &S.kb);
+    if (st_mark) mark(m, PF_SORT, st_mark);
+
+    SegProb so = seg_prob(m, S, 0, (int)w.O), si = seg_prob(m, S, 1, w.b.n_centers);
+    so.row_ids = out.ids;
+    so.n_rows = out.n_rows;
+    so.seg_offsets = out.offsets;
+    so.capacity = out.capacity;
+    si.row_ids = in.ids;
+    si.n_rows = in.n_rows;
+    si.seg_offsets = in.offsets;
+    si.capacity = in.capacity;
+    tn_launch_segments(so, si, w.b.begin, w.b.T, c.window, m->status, st);
+    if (st_mark) mark(m, PF_SEGMENTS, st_mark);
+}
+
+static int check_batch(const tensair_model *m, const int32_t *tokens, i64 n_tokens, i64 center_begin, int n_centers,
+                       u32 epoch)
+{
+    if (!tokens) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    if (n_tokens < 1 || center_begin < 0 || n_centers < 0 || center_begin + n_centers > n_tokens)
+        return fail(TENSAIR_EINVAL, "center range [%lld, +%d) outside the stream of %lld tokens",
+                    (long long)center_begin, n_centers, (long long)n_tokens);
+    if (n_centers > m->cfg.max_centers)
+        return fail(TENSAIR_ECAPACITY, "n_centers %d > max_centers %d", n_centers, m->cfg.max_centers);
+    if (epoch >= 65536u) return fail(TENSAIR_EINVAL, "epoch must be below 65536");
+    return TENSAIR_OK;
+}
+
+// Enqueue the preparation of an announced mini-batch on the second stream, into the set that the
+// latest gradient call does not read.  The second stream must already be behind that set's last readers.
+static int enqueue_prepare(tensair_model *m, const Prefetched &d)
+{
+    const tensair_config &c = m->cfg;
+    BatchSet &S = m->set[1 - m->busy];
+    const BatchWork w = batch_work(c, d.tokens, d.n_tokens, d.begin, d.n_centers, d.epoch, d.P);
+    enqueue_keys(m, S, w, nullptr, m->side);
+    const RowIndexDst in = {S.ids_in, S.n_rows, S.off_in, tensair_capacity_in(&c, c.max_centers)};
+    const RowIndexDst out = {S.ids_out, S.n_rows + 1, S.off_out, tensair_capacity_out(&c, c.max_centers)};
+    enqueue_sort_segments(m, S, w, in, out, m->side, nullptr);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(m->ev_prep, m->side));
+    m->prep_ticket = ++m->side_ticket;
+    m->pend = d;
+    return TENSAIR_OK;
+}
+
+int tensair_prefetch(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                     int32_t n_centers, uint32_t epoch, void *stream)
+{
+    if (!m) return fail(TENSAIR_EINVAL, "model is NULL");
+    int rc = check_batch(m, tokens, n_tokens, center_begin, n_centers, epoch);
+    if (rc) return rc;
+    const tensair_config &c = m->cfg;
+    Prefetched d;
+    d.tokens = tokens;
+    d.n_tokens = n_tokens;
+    d.begin = center_begin;
+    d.n_centers = n_centers;
+    d.epoch = epoch;
+    d.worker_id = c.worker_id;
+    d.P = pair_count(c, n_tokens, center_begin, n_centers);
+    if (d.P == 0) return TENSAIR_OK;   // nothing to prepare
+    d.valid = true;
+    if (m->pend.valid) {   // one mini-batch is waiting already: this one is prepared when that is consumed
+        m->next = d;
+        return TENSAIR_OK;
+    }
+    // The set being filled was last read by the gradient call before the latest one.  If the second
+    // stream has waited for the start of the latest call it is already behind those readers; if not,
+    // it is put behind everything enqueued on the caller's stream so far.
+    if (!m->side_follows) {
+        hipStream_t st = (hipStream_t)stream;
+        HIP_TRY(hipEventRecord(m->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+        m->side_follows = true;
+    }
+    return enqueue_prepare(m, d);
+}
+
 int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
                       int32_t n_centers, uint32_t epoch, tensair_sparse_grad *grad_out, float *mean_loss,
                       int32_t *negatives_dbg, int32_t *seg_offsets_in, int32_t *seg_offsets_out, void *stream)
 {
-    if (!m || !tokens || !grad_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    if (!m || !grad_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     const tensair_config &c = m->cfg;
-    if (n_tokens < 1 || center_begin < 0 || n_centers < 0 || center_begin + n_centers > n_tokens)
-        return fail(TENSAIR_EINVAL, "center range [%lld, +%d) outside the stream of %lld tokens",
-                    (long long)center_begin, n_centers, (long long)n_tokens);
-    if (n_centers > c.max_centers)
-        return fail(TENSAIR_ECAPACITY, "n_centers %d > max_centers %d", n_centers, c.max_centers);
-    if (epoch >= 65536u) return fail(TENSAIR_EINVAL, "epoch must be below 65536");
-    int rc;
+    int rc = check_batch(m, tokens, n_tokens, center_begin, n_centers, epoch);
+    if (rc) return rc;
     if ((rc = check_rows(grad_out->in, tensair_capacity_in(&c, n_centers), "grad_out.in"))) return rc;
     if ((rc = check_rows(grad_out->out, tensair_capacity_out(&c, n_centers), "grad_out.out"))) return rc;
     hipStream_t st = (hipStream_t)stream;
@@ -377,38 +582,37 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
         return TENSAIR_OK;
     }
     const int Np1 = c.negatives + 1;
-    const i64 O = P * Np1;
-
-    BatchDesc b;
-    b.tok = tokens;
-    b.T = n_tokens;
-    b.begin = center_begin;
-    b.n_centers = n_centers;
-    b.w = c.window;
-    b.N = c.negatives;
-    b.pair_base = pairs_before(center_begin, n_tokens, c.window);
-    b.P = P;
+    const BatchWork w = batch_work(c, tokens, n_tokens, center_begin, n_centers, epoch, P);
 
     // Streams.  The sort and the segment scan only need the keys, the forward pass the keys and the
-    // tables, the reductions both: the sort runs on the library's second stream next to the forward
-    // pass (fork/join by events).  Inside tensair_step the second stream then builds the index of
-    // the coming apply while the reductions run on the caller's stream.  When
-    // every stage is being timed (profile level 2) everything is serialised on the caller's stream.
+    // tables, the reductions both.  Without a prefetch the chain that the apply waits for (keys, sort,
+    // segments, reductions) stays on the caller's stream, so that none of its links is a cross-stream
+    // wait, and the forward pass runs next to the sort on the library's second stream.  With a matching
+    // prefetch the keys, the sorted order and the segments are already there (made on the second stream
+    // while the previous step ran) and the caller's stream starts with the forward pass.  Either way,
+    // inside tensair_step the second stream builds the index of the coming apply meanwhile.  When every
+    // stage is being timed (profile level 2) everything is serialised on the caller's stream.
     const bool overlap = m->prof_level < 2;
     const bool fuse = overlap && m->fused_apply != nullptr;
-    hipStream_t s_sort = overlap ? m->side : st;
-    mark(m, PF_BEGIN_GRAD, st);
-    // 1. keys: out-side occurrences at [0, O), in-side centers at [Omax, Omax + n_centers)
-    tn_launch_build_keys(b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, epoch, m->keys[0],
-                         m->keys[0] + s.Omax, m->pair_center, negatives_dbg, m->status, st);
-    mark(m, PF_KEYS, st);
-    if (overlap) {
-        HIP_TRY(hipEventRecord(m->ev_fork, st));
-        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+    const bool prepared = overlap && negatives_dbg == nullptr &&
+                          m->pend.is(tokens, n_tokens, center_begin, n_centers, epoch, c.worker_id);
+    m->pend.valid = false;
+    // the announced mini-batch after this one is prepared during this call; announcements that this
+    // call does not follow are dropped
+    const Prefetched following = prepared ? m->next : Prefetched();
+    m->next.valid = false;
+    // this call takes the set that announced mini-batches are prepared into; one that does not match
+    // is overwritten, after its preparation has finished
+    const int u = 1 - m->busy;
+    BatchSet &S = m->set[u];
+    if (m->prep_ticket > m->main_ticket) {
+        HIP_TRY(hipStreamWaitEvent(st, m->ev_prep, 0));
+        m->main_ticket = m->prep_ticket;
     }
+    m->busy = u;
+    m->side_follows = false;
+    mark(m, PF_BEGIN_GRAD, st);
 
-    // 2. forward on the unsorted keys (the sort never writes their buffer): g per occurrence,
-    //    per-center share of the W_in gradient, loss terms
     FwdArgs f;
     f.w_in = m->w_in;
     f.w_out = m->w_out;
@@ -416,114 +620,123 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     f.dtype = c.dtype;
     f.D = c.dim;
     f.stride = c.row_stride;
-    f.b = b;
-    f.out_keys = m->keys[0];
+    f.b = w.b;
+    f.out_keys = S.keys[0];
     f.g = m->g;
     f.center_part = m->center_part;
     f.center_loss = mean_loss ? m->center_loss : nullptr;   // loss terms only on request
     f.inv_P = 1.0f / (float)P;
-    tn_launch_forward(f, st);
-    if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
-    mark(m, PF_FORWARD, st);
 
-    // 3. stable sort of both key lists by row id
-    RadixProb ro, ri;
-    for (int i = 0; i < 3; ++i) {
-        ro.keys[i] = m->keys[i];
-        ri.keys[i] = m->keys[i] + s.Omax;
-    }
-    for (int i = 0; i < 2; ++i) {
-        ro.vals[i] = m->vals[i];
-        ri.vals[i] = m->vals[i] + s.Omax;
-    }
-    ro.n = (int)O;
-    ro.nblk = (int)((O + TN_RADIX_TILE - 1) / TN_RADIX_TILE);
-    ro.counts = m->counts_out;
-    ro.totals = m->totals_out;
-    ri.n = n_centers;
-    ri.nblk = (n_centers + TN_RADIX_TILE - 1) / TN_RADIX_TILE;
-    ri.counts = m->counts_in;
-    ri.totals = m->totals_in;
-    int kb = 1;
-    const int cur = tn_launch_radix_sort(ro, ri, s.key_bits, s_sort, &kb);
-    mark(m, PF_SORT, st);
-
-    // 4. unique row ids, segment index per sorted entry
-    SegProb so, si;
-    so.keys = ro.keys[kb];
-    so.vals = ro.vals[cur];
-    so.n = (int)O;
-    so.nblk = (int)((O + TN_SCAN_TILE - 1) / TN_SCAN_TILE);
-    so.blk_heads = m->blk_heads;
-    so.blk_weight = m->blk_weight;
-    so.seg_of = m->seg_of;
-    so.seg_start = m->seg_start;
-    so.long_cnt = m->long_cnt;
-    so.row_ids = grad_out->out.row_ids;
-    so.n_rows = grad_out->out.n_rows;
-    so.seg_offsets = seg_offsets_out;
-    so.capacity = grad_out->out.capacity;
-    so.weighted = 0;
-    si.keys = ri.keys[kb];
-    si.vals = ri.vals[cur];
-    si.n = n_centers;
-    si.nblk = (n_centers + TN_SCAN_TILE - 1) / TN_SCAN_TILE;
-    si.blk_heads = m->blk_heads + s.sblk_out;
-    si.blk_weight = m->blk_weight + s.sblk_out;
-    si.seg_of = m->seg_of + s.Omax;
-    si.seg_start = m->seg_start + s.Omax + 1;
-    si.long_cnt = m->long_cnt + 1;
-    si.row_ids = grad_out->in.row_ids;
-    si.n_rows = grad_out->in.n_rows;
-    si.seg_offsets = seg_offsets_in;
-    si.capacity = grad_out->in.capacity;
-    si.weighted = 1;
-    tn_launch_segments(so, si, center_begin, n_tokens, c.window, m->status, s_sort);
-    mark(m, PF_SEGMENTS, st);
-    if (overlap) {
-        HIP_TRY(hipEventRecord(m->ev_join, m->side));
-        HIP_TRY(hipStreamWaitEvent(st, m->ev_join, 0));
-    }
-    if (fuse) {   // off the critical path: the reductions run meanwhile, the apply waits for ev_index
-        tn_launch_apply_clear(*m->fused_apply, m->side);
-        tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
+    if (prepared) {
+        // second stream: this mini-batch's row index to the caller's buffers and the index of the coming
+        // apply, then the preparation of the following mini-batch
+        HIP_TRY(hipEventRecord(m->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+        m->side_follows = true;
+        RowIndexCopy rc2;
+        rc2.side[0] = {S.ids_in, S.n_rows, S.off_in, grad_out->in.row_ids, grad_out->in.n_rows, seg_offsets_in};
+        rc2.side[1] = {S.ids_out, S.n_rows + 1, S.off_out, grad_out->out.row_ids, grad_out->out.n_rows,
+                       seg_offsets_out};
+        tn_launch_copy_row_index(rc2, tensair_capacity_out(&c, n_centers), m->side);
+        if (fuse) {
+            tn_launch_apply_clear(*m->fused_apply, m->side);
+            tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
+            m->fused_index_done = true;
+        }
         HIP_TRY(hipEventRecord(m->ev_index, m->side));
-        m->fused_index_done = true;
+        m->index_ticket = ++m->side_ticket;
+        if (following.valid && !(fuse && m->prepare_under_apply) && (rc = enqueue_prepare(m, following))) return rc;
+        // caller's stream: forward pass on the prepared keys
+        tn_launch_forward(f, st);
+        if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
+    } else {
+        // 1. keys
+        enqueue_keys(m, S, w, negatives_dbg, st);
+        mark(m, PF_KEYS, st);
+        hipStream_t s_fwd = st;
+        if (overlap) {
+            HIP_TRY(hipEventRecord(m->ev_fork, st));
+            HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+            m->side_follows = true;
+            s_fwd = m->side;
+        }
+        // 2. forward on the unsorted keys (the sort never writes their buffer): g per occurrence,
+        //    per-center share of the W_in gradient, loss terms
+        tn_launch_forward(f, s_fwd);
+        if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, s_fwd);
+        mark(m, PF_FORWARD, st);
+        if (overlap) {
+            HIP_TRY(hipEventRecord(m->ev_fwd, m->side));
+            if (fuse) tn_launch_apply_clear(*m->fused_apply, m->side);
+        }
+        // 3./4. sort and segments, row index straight into the caller's buffers
+        const RowIndexDst in = {grad_out->in.row_ids, grad_out->in.n_rows, seg_offsets_in, grad_out->in.capacity};
+        const RowIndexDst out = {grad_out->out.row_ids, grad_out->out.n_rows, seg_offsets_out,
+                                 grad_out->out.capacity};
+        enqueue_sort_segments(m, S, w, in, out, st, st);
+        if (fuse) {   // off the critical path: the reductions run meanwhile, the apply waits for ev_index
+            HIP_TRY(hipEventRecord(m->ev_segs, st));
+            HIP_TRY(hipStreamWaitEvent(m->side, m->ev_segs, 0));
+            tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
+            HIP_TRY(hipEventRecord(m->ev_index, m->side));
+            m->index_ticket = ++m->side_ticket;
+            m->fused_index_done = true;
+        }
+        if (overlap) HIP_TRY(hipStreamWaitEvent(st, m->ev_fwd, 0));
     }
 
     // 5. segmented reductions: duplicates of a row summed in sorted (= occurrence) order
-    SegReduceArgs r;
-    memset(&r, 0, sizeof(r));
-    r.D = c.dim;
-    r.n = n_centers;
-    r.vals = si.vals;
-    r.seg_of = si.seg_of;
-    r.seg_start = si.seg_start;
-    r.long_cnt = si.long_cnt;
-    r.long_list = m->long_list + s.tiles_out;
-    r.out_rows = grad_out->in.row_grads;
-    r.part = m->part_in;
-    r.mode = 1;
-    r.center_part = m->center_part;
-    tn_launch_segreduce(r, st);
-    mark(m, PF_REDUCE_IN, st);
-    r.n = (int)O;
-    r.vals = so.vals;
-    r.seg_of = so.seg_of;
-    r.seg_start = so.seg_start;
-    r.long_cnt = so.long_cnt;
-    r.long_list = m->long_list;
-    r.out_rows = grad_out->out.row_grads;
-    r.part = m->part_out;
-    r.mode = 0;
-    r.g = m->g;
-    r.pair_center = m->pair_center;
-    r.Np1 = Np1;
-    r.table = m->w_in;
-    r.dtype = c.dtype;
-    r.stride = c.row_stride;
-    tn_launch_segreduce(r, st);
+    const SegProb so = seg_prob(m, S, 0, (int)w.O), si = seg_prob(m, S, 1, n_centers);
+    SegReduceArgs r_in, r_out;
+    memset(&r_in, 0, sizeof(r_in));
+    r_in.D = c.dim;
+    r_in.n = n_centers;
+    r_in.vals = si.vals;
+    r_in.seg_of = si.seg_of;
+    r_in.seg_start = si.seg_start;
+    r_in.long_cnt = si.long_cnt;
+    r_in.long_list = m->long_list + s.tiles_out;
+    r_in.out_rows = grad_out->in.row_grads;
+    r_in.part = m->part_in;
+    r_in.mode = 1;
+    r_in.center_part = m->center_part;
+    r_out = r_in;
+    r_out.n = (int)w.O;
+    r_out.vals = so.vals;
+    r_out.seg_of = so.seg_of;
+    r_out.seg_start = so.seg_start;
+    r_out.long_cnt = so.long_cnt;
+    r_out.long_list = m->long_list;
+    r_out.out_rows = grad_out->out.row_grads;
+    r_out.part = m->part_out;
+    r_out.mode = 0;
+    r_out.g = m->g;
+    r_out.pair_center = S.pair_center;
+    r_out.Np1 = Np1;
+    r_out.table = m->w_in;
+    r_out.dtype = c.dtype;
+    r_out.stride = c.row_stride;
+    if (overlap) {   // both sides in one launch
+        tn_launch_segreduce(&r_out, &r_in, st);
+    } else {         // one after the other, so that each can be timed
+        tn_launch_segreduce(nullptr, &r_in, st);
+        mark(m, PF_REDUCE_IN, st);
+        tn_launch_segreduce(&r_out, nullptr, st);
+    }
     mark(m, PF_REDUCE_OUT, st);
+    // the row index copied on the second stream belongs to this call's results
+    if (prepared && !fuse) {
+        HIP_TRY(hipStreamWaitEvent(st, m->ev_index, 0));
+        m->main_ticket = m->index_ticket;
+    }
+    // Where a long table update follows (tensair_step decides), the following mini-batch is prepared
+    // behind this call's reductions: next to them it would slow them down, next to the update, which is
+    // bound by HBM bandwidth, it costs little.  Otherwise it was enqueued above, next to the forward pass.
+    if (following.valid && fuse && m->prepare_under_apply) {
+        HIP_TRY(hipEventRecord(m->ev_reduced, st));
+        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_reduced, 0));
+        if ((rc = enqueue_prepare(m, following))) return rc;
+    }
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }
@@ -602,6 +815,15 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
     if (rc) return rc;
     m->fused_apply = &a;
     m->fused_index_done = false;
+    {   // rough times of the table update (bytes of the gradient blocks at their largest, at 5 TB/s) and of
+        // the preparation of a mini-batch (0.2 ns per occurrence plus its launches)
+        const tensair_config &c = m->cfg;
+        const double occ = 2.0 * c.window * (double)n_centers * (c.negatives + 1);
+        const double rows = occ < (double)c.vocab ? occ : (double)c.vocab;
+        const double t_apply = (double)a.n_src * rows * c.dim * 4.0 / 5e12;
+        const double t_prepare = occ * 0.2e-9 + 60e-6;
+        m->prepare_under_apply = t_apply >= 2.0 * t_prepare;
+    }
     rc = tensair_sgns_grad(m, tokens, n_tokens, center_begin, n_centers, epoch, own_out, mean_loss, nullptr,
                            nullptr, nullptr, stream);
     m->fused_apply = nullptr;
@@ -610,6 +832,7 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
     mark(m, PF_BEGIN_APPLY, st);
     if (m->fused_index_done) {
         HIP_TRY(hipStreamWaitEvent(st, m->ev_index, 0));
+        m->main_ticket = m->index_ticket;
     } else {
         tn_launch_apply_clear(a, st);
         tn_launch_apply_index(a, 0, a.n_src, st);
@@ -638,15 +861,6 @@ int tensair_status(tensair_model *m, void *stream)
     }
     return TENSAIR_OK;
 }
-
-#ifdef TENSAIR_DEBUG
-extern "C" int tensair_debug_ptrs(tensair_model *m, void **out)
-{
-    out[0] = m->part_out; out[1] = m->part_in; out[2] = m->seg_of; out[3] = m->seg_start;
-    out[4] = m->vals[0]; out[5] = m->vals[1]; out[6] = m->g; out[7] = m->pair_center;
-    return 0;
-}
-#endif
 
 int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
 {
@@ -692,9 +906,15 @@ int tensair_model_destroy(tensair_model *m)
     if (m) {
         for (hipEvent_t ev : m->prof_pool) (void)hipEventDestroy(ev);
         if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
-        if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+        if (m->ev_fwd) (void)hipEventDestroy(m->ev_fwd);
+        if (m->ev_segs) (void)hipEventDestroy(m->ev_segs);
         if (m->ev_index) (void)hipEventDestroy(m->ev_index);
-        if (m->side) (void)hipStreamDestroy(m->side);
+        if (m->ev_prep) (void)hipEventDestroy(m->ev_prep);
+        if (m->ev_reduced) (void)hipEventDestroy(m->ev_reduced);
+        if (m->side) {
+            (void)hipStreamSynchronize(m->side);   // a pending prefetch still writes the workspace
+            (void)hipStreamDestroy(m->side);
+        }
     }
     delete m;
     return TENSAIR_OK;

@@ -137,8 +137,12 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
     store_row<T, ITERS>(wrow, w, C4, lane);
 }
 
+#ifndef APPLY_MAX_WAVES
+#define APPLY_MAX_WAVES 6
+#endif
 template <typename T, int ITERS, int G>
-__global__ void __launch_bounds__(BLOCK) k_apply(ApplyArgs a, int nblocks)
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(1, APPLY_MAX_WAVES)))
+k_apply(ApplyArgs a, int nblocks)
 {
     // keep runs of APPLY_CHUNK consecutive workgroups on one XCD (workgroups are dealt
     // round-robin to the 8 XCDs), so that neighbouring rows -- which share cache lines when

@@ -12,6 +12,8 @@
 //             a wave sums, in sorted order, the short rows that begin in its tile and its share
 //             of long rows, whose partials a second kernel chains in tile order.  Load balance
 //             is therefore independent of how hot a row is.
+#include <string.h>
+
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -161,11 +163,11 @@ __device__ __forceinline__ void entry_source(const SegReduceArgs &a, u32 val, co
 // began in an earlier tile, part[tile][1] for one that begins here), and k_segfixup chains the
 // partials in tile order.  Work per wave is bounded by 2*TILE entries whatever the skew of the ids.
 template <typename T, int ITERS, int MODE, int TILE>
-__global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
+__device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block)
 {
     static_assert(2 * TILE <= WAVE, "a wave keeps the metadata of two tiles in its lanes");
     // the wave index is made explicitly wave-uniform so that all the control flow below is scalar
-    const int tile = blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6));
+    const int tile = block * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int t0 = tile * TILE;
     if (t0 >= a.n) return;
@@ -268,20 +270,36 @@ __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReduceArgs a)
     if (dest == 2 && lane == 0) a.long_list[atomicAdd(a.long_cnt, 1)] = tile;
 }
 
+// The W_out-side and the W_in-side reduction of a mini-batch are independent: one launch runs both
+// (workgroups [0, blocks_in) take the in-side problem, the rest the out-side one), so that the small
+// in-side problem costs no launch of its own and its few workgroups start first.
+struct SegReducePair {
+    SegReduceArgs out, in;
+    int blocks_in;   // workgroups of the in-side problem at the front of the grid
+};
+
+template <typename T, int ITERS, int TILE_OUT, int TILE_IN>
+__global__ void __launch_bounds__(BLOCK) k_segreduce(SegReducePair p)
+{
+    const int b = blockIdx.x;
+    if (b < p.blocks_in) segreduce_tile<float, ITERS, 1, TILE_IN>(p.in, b);
+    else segreduce_tile<T, ITERS, 0, TILE_OUT>(p.out, b - p.blocks_in);
+}
+
 // Chains the partials of long rows in tile order: one workgroup per long row (grid-strided
 // over the list the reduction left), its waves sharing the chain part[tile][1], part[tile+1][0], ...
-template <int ITERS, int TILE>
 // (512-thread workgroups: 1024-thread ones wait for a whole compute unit's worth of free wave
 // slots when another kernel fills the chip, which starved this kernel for hundreds of microseconds)
 #define FIXUP_THREADS 512
-__global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReduceArgs a)
+template <int ITERS, int TILE>
+__device__ __forceinline__ void segfixup_rows(const SegReduceArgs &a, int first, int stride,
+                                              float (*red)[ITERS * WAVE * 4])
 {
     constexpr int NW = FIXUP_THREADS / WAVE;
-    __shared__ float red[NW][ITERS * WAVE * 4];
     const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const int C4 = a.D >> 2;
     const int count = *a.long_cnt;
-    for (int i = blockIdx.x; i < count; i += gridDim.x) {
+    for (int i = first; i < count; i += stride) {
         const int tile = a.long_list[i];
         const int t1 = min(a.n, tile * TILE + TILE);
         const int row = a.seg_of[t1 - 1];
@@ -321,38 +339,65 @@ __global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReduceArgs a)
     }
 }
 
-template <typename T, int MODE, int ITERS, int TILE>
-static void launch_segreduce_i(const SegReduceArgs &a, hipStream_t st)
+template <int ITERS, int TILE_OUT, int TILE_IN>
+__global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReducePair p)
 {
-    int ntiles = (a.n + TILE - 1) / TILE;
-    dim3 grid((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), blk(BLOCK);
-    hipLaunchKernelGGL((k_segreduce<T, ITERS, MODE, TILE>), grid, blk, 0, st, a);
-    if (ntiles > 1) {
-        int fb = ntiles < 1024 ? ntiles : 1024;
-        hipLaunchKernelGGL((k_segfixup<ITERS, TILE>), dim3(fb), dim3(FIXUP_THREADS), 0, st, a);
+    __shared__ float red[FIXUP_THREADS / WAVE][ITERS * WAVE * 4];
+    const int b = blockIdx.x;
+    if (b < p.blocks_in) segfixup_rows<ITERS, TILE_IN>(p.in, b, p.blocks_in, red);
+    else segfixup_rows<ITERS, TILE_OUT>(p.out, b - p.blocks_in, (int)gridDim.x - p.blocks_in, red);
+}
+
+template <typename T, int ITERS, int TILE_OUT, int TILE_IN>
+static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
+{
+    const int tiles_out = p.out.n > 0 ? (p.out.n + TILE_OUT - 1) / TILE_OUT : 0;
+    const int tiles_in = p.in.n > 0 ? (p.in.n + TILE_IN - 1) / TILE_IN : 0;
+    const int blocks_out = (tiles_out + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    p.blocks_in = (tiles_in + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    hipLaunchKernelGGL((k_segreduce<T, ITERS, TILE_OUT, TILE_IN>), dim3(p.blocks_in + blocks_out), dim3(BLOCK), 0,
+                       st, p);
+    // long rows exist only where a problem has more than one tile
+    const int fix_out = tiles_out > 1 ? (tiles_out < 1024 ? tiles_out : 1024) : 0;
+    const int fix_in = tiles_in > 1 ? (tiles_in < 1024 ? tiles_in : 1024) : 0;
+    if (fix_out + fix_in > 0) {
+        p.blocks_in = fix_in;
+        hipLaunchKernelGGL((k_segfixup<ITERS, TILE_OUT, TILE_IN>), dim3(fix_out + fix_in), dim3(FIXUP_THREADS), 0,
+                           st, p);
     }
 }
 
-template <typename T, int MODE>
-static void launch_segreduce_t(const SegReduceArgs &a, hipStream_t st)
+template <typename T, int ITERS>
+static void launch_segreduce_t(SegReducePair &p, hipStream_t st)
 {
-    int C4 = a.D / 4;
-    int iters = (C4 + WAVE - 1) / WAVE;
-    const bool small = tn_seg_tile(a.n) == 8;
+    const bool so = tn_seg_tile(p.out.n) == 8, si = tn_seg_tile(p.in.n) == 8;
+    if (so) si ? launch_segreduce_i<T, ITERS, 8, 8>(p, st) : launch_segreduce_i<T, ITERS, 8, 32>(p, st);
+    else si ? launch_segreduce_i<T, ITERS, 32, 8>(p, st) : launch_segreduce_i<T, ITERS, 32, 32>(p, st);
+}
+
+template <typename T>
+static void launch_segreduce_d(SegReducePair &p, int D, hipStream_t st)
+{
+    const int iters = (D / 4 + WAVE - 1) / WAVE;
     switch (iters) {
-    case 1: small ? launch_segreduce_i<T, MODE, 1, 8>(a, st) : launch_segreduce_i<T, MODE, 1, 32>(a, st); break;
-    case 2: small ? launch_segreduce_i<T, MODE, 2, 8>(a, st) : launch_segreduce_i<T, MODE, 2, 32>(a, st); break;
-    case 3: small ? launch_segreduce_i<T, MODE, 3, 8>(a, st) : launch_segreduce_i<T, MODE, 3, 32>(a, st); break;
-    default: small ? launch_segreduce_i<T, MODE, 4, 8>(a, st) : launch_segreduce_i<T, MODE, 4, 32>(a, st); break;
+    case 1: launch_segreduce_t<T, 1>(p, st); break;
+    case 2: launch_segreduce_t<T, 2>(p, st); break;
+    case 3: launch_segreduce_t<T, 3>(p, st); break;
+    default: launch_segreduce_t<T, 4>(p, st); break;
     }
 }
 
-void tn_launch_segreduce(const SegReduceArgs &a, hipStream_t st)
+// Either problem may be absent (NULL): the other one then runs alone.
+void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, hipStream_t st)
 {
-    if (a.n <= 0) return;
-    if (a.mode == 1) launch_segreduce_t<float, 1>(a, st);
-    else if (a.dtype == 0) launch_segreduce_t<float, 0>(a, st);
-    else launch_segreduce_t<bf16_t, 0>(a, st);
+    SegReducePair p;
+    memset(&p, 0, sizeof(p));
+    if (out && out->n > 0) p.out = *out;
+    if (in && in->n > 0) p.in = *in;
+    if (p.out.n <= 0 && p.in.n <= 0) return;
+    const int D = p.out.n > 0 ? p.out.D : p.in.D;
+    if (p.out.n > 0 && p.out.dtype != 0) launch_segreduce_d<bf16_t>(p, D, st);
+    else launch_segreduce_d<float>(p, D, st);
 }
 
 // ---------------------------------------------------------------- loss and the empty batch

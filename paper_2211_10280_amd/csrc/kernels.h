@@ -65,6 +65,15 @@ struct SegProb {
 };
 void tn_launch_segments(SegProb p0, SegProb p1, i64 begin, i64 T, int w, int *status, hipStream_t st);
 
+// row ids / row count / segment offsets of a prepared mini-batch -> the consuming call's buffers
+struct RowIndexCopy {
+    struct Side {
+        const int *src_ids, *src_n, *src_off;   // src_off [U+1]
+        int *dst_ids, *dst_n, *dst_off;         // dst_off may be NULL
+    } side[2];
+};
+void tn_launch_copy_row_index(const RowIndexCopy &c, i64 max_rows, hipStream_t st);
+
 // ---- stage 4: forward pass and per-center partial of the W_in gradient
 struct FwdArgs {
     const void *w_in, *w_out;
@@ -101,7 +110,8 @@ struct SegReduceArgs {
     int dtype, stride;
     const float *center_part;
 };
-void tn_launch_segreduce(const SegReduceArgs &a, hipStream_t st);
+// the W_out-side and the W_in-side problem of a mini-batch in one launch (either may be NULL)
+void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, hipStream_t st);
 
 void tn_launch_loss(const float *center_loss, int n_centers, float inv_P, float *mean_loss,
                     hipStream_t st);

@@ -345,3 +345,24 @@ void tn_launch_segments(SegProb p0, SegProb p1, i64 begin, i64 T, int w, int *st
     hipLaunchKernelGGL(k_head_count, dim3(nblk), dim3(BLOCK), 0, st, a);
     hipLaunchKernelGGL(k_seg_assign, dim3(nblk), dim3(BLOCK), 0, st, a);
 }
+
+// ---------------------------------------------------------------- hand-over of prepared row ids
+// Row ids, row count and segment offsets of a mini-batch whose sort ran ahead of time sit in the
+// workspace; this copies them into the buffers of the call that consumes them.
+__global__ void __launch_bounds__(BLOCK) k_copy_row_index(RowIndexCopy c)
+{
+    const RowIndexCopy::Side &s = c.side[blockIdx.y];
+    const int U = *s.src_n;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *s.dst_n = U;
+    for (int i = blockIdx.x * BLOCK + threadIdx.x; i <= U; i += gridDim.x * BLOCK) {
+        if (i < U) s.dst_ids[i] = s.src_ids[i];
+        if (s.dst_off) s.dst_off[i] = s.src_off[i];
+    }
+}
+
+void tn_launch_copy_row_index(const RowIndexCopy &c, i64 max_rows, hipStream_t st)
+{
+    i64 want = (max_rows + 1 + BLOCK - 1) / BLOCK;
+    int blocks = (int)(want > 1024 ? 1024 : want);
+    hipLaunchKernelGGL(k_copy_row_index, dim3(blocks, 2), dim3(BLOCK), 0, st, c);
+}

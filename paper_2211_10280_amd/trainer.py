@@ -20,8 +20,10 @@ from . import workload as W
 
 
 class DasgdWorker:
-    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda"):
+    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True):
         self.cfg = cfg
+        self.prefetch = prefetch     # announce coming mini-batches with tensair_prefetch
+        self.announced = -1          # last step whose mini-batch has been announced
         self.device = device
         dt = B.F32 if cfg.dtype == "f32" else B.BF16
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
@@ -73,10 +75,28 @@ class DasgdWorker:
         if peers is None:
             peers = self.make_peer_grads(t) if cfg.peers else []
         begin, n, epoch = W.worker_batch(cfg, t, 0)
+        # the worker's coming mini-batches are already waiting in its input queue: once this step's
+        # mini-batch has been announced, the next one is announced before the step, so that the library
+        # prepares it during the step
+        if self.prefetch and self.announced == t:
+            self._announce(t + 1)
         self.model.step(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
                         self.mean_loss if want_loss else None)
         self.step_no += 1
+        if self.prefetch and self.announced < t + 1:
+            self._announce(t + 1)
         return begin, n, epoch
+
+    def _announce(self, t):
+        begin, n, epoch = W.worker_batch(self.cfg, t, 0)
+        self.model.prefetch(self.tokens, begin, n, epoch)
+        self.announced = t
+
+    def restart(self):
+        """Back to step 0 (the tables are the caller's business); pending announcements no longer
+        match and are dropped by the library at the next step."""
+        self.step_no = 0
+        self.announced = -1
 
     def tables_to_host(self):
         w_in, w_out = self.model.w_in, self.model.w_out

@@ -264,9 +264,9 @@ def test_apply_is_eq1_and_merged_equals_sequential():
 
 
 # ------------------------------------------------------------------ multi-step runs (train)
-def _run_both(cfg, steps, threads=8):
+def _run_both(cfg, steps, threads=8, prefetch=True):
     tok, counts = W.make_stream(cfg)
-    gw = DasgdWorker(cfg, tok, counts)
+    gw = DasgdWorker(cfg, tok, counts, prefetch=prefetch)
     ow = OracleWorker(cfg, tok, counts, threads=threads)
     W0_in, W0_out = ow.W_in.copy(), ow.W_out.copy()
     g_in0, g_out0 = gw.tables_to_host()
@@ -325,12 +325,14 @@ def test_train_config1_full_pass():
     ("cfg4_small", dict(vocab=500, tokens=200_000, batch=1024), 4),
     ("cfg5_small", dict(vocab=20_000, tokens=300_000, batch=256), 5),
 ])
-def test_train_scaled_configs(name, kw, steps):
+@pytest.mark.parametrize("prefetch", [True, False], ids=["prefetch", "inline"])
+def test_train_scaled_configs(name, kw, steps, prefetch):
     """The shapes of configurations 2-5 (dim, window, negatives, peers, staleness, dtype) at a vocabulary
-    and batch the oracle finishes in seconds; several radix/segment tiles and ragged tails."""
+    and batch the oracle finishes in seconds; several radix/segment tiles and ragged tails.  Once with the
+    next mini-batch prefetched after every step, once with every step self-contained."""
     base = W.CONFIGS[int(name[3])]
-    _say("train", name)
-    _run_both(base.scaled(name=name, **kw), steps)
+    _say("train", name, "prefetch" if prefetch else "inline")
+    _run_both(base.scaled(name=name, **kw), steps, prefetch=prefetch)
 
 
 @pytest.mark.parametrize("idx,steps", [(2, 6), (3, 5), (4, 2), (5, 2)])
@@ -338,6 +340,119 @@ def test_train_full_size_configs(idx, steps):
     """Configurations 2-5 at their full sizes, in the launch configuration the benchmark times."""
     _say("train full size", idx)
     _run_both(W.CONFIGS[idx], steps)
+
+
+# ------------------------------------------------------------------ prefetch of the coming mini-batch
+def _grad_snapshot(g, loss=None, seg_in=None, seg_out=None):
+    ui, uo = g.sizes()
+    out = [ui, uo, g.in_ids[:ui].cpu().numpy().copy(), g.out_ids[:uo].cpu().numpy().copy(),
+           g.in_rows[:ui].cpu().numpy().copy(), g.out_rows[:uo].cpu().numpy().copy()]
+    if loss is not None:
+        out.append(loss.cpu().numpy().copy())
+    if seg_in is not None:
+        out += [seg_in[: ui + 1].cpu().numpy().copy(), seg_out[: uo + 1].cpu().numpy().copy()]
+    return out
+
+
+def _same(a, b):
+    return len(a) == len(b) and all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_prefetch_gives_the_same_bits():
+    """tensair_prefetch only moves work in time: a gradient call that consumes it returns exactly what
+    a call without it returns; a prefetch for another mini-batch is dropped."""
+    V, D, T, w, N, Bc = 5000, 300, 40_000, 5, 10, 512
+    tok = W.zipf_stream(V, 1.1, T, 5)
+    counts = W.unigram_counts(tok, V)
+    Wi, Wo = _random_tables(V, D, D, "f32", seed=11)
+    m = B.Model(V, D, B.F32, w, N, Bc, 0, 77, counts, worker_id=2, tables=(_tables_to_dev(Wi, "f32"),
+                                                                          _tables_to_dev(Wo, "f32")))
+    dtok = torch.from_numpy(tok).cuda()
+    g = m.grad_buffers()
+    loss = torch.zeros(1, device="cuda")
+    seg_in = torch.zeros(g.cap_in + 1, dtype=torch.int32, device="cuda")
+    seg_out = torch.zeros(g.cap_out + 1, dtype=torch.int32, device="cuda")
+    kw = dict(mean_loss=loss, seg_offsets_in=seg_in, seg_offsets_out=seg_out)
+
+    def plain(begin, n, epoch):
+        m.sgns_grad(dtok, begin, n, epoch, g, **kw)
+        return _grad_snapshot(g, loss, seg_in, seg_out)
+
+    ref_a, ref_b, ref_c = plain(1024, 512, 1), plain(1536, 300, 1), plain(0, 100, 0)
+    for buf in (g.in_ids, g.out_ids, g.in_rows, g.out_rows, g.n_rows, seg_in, seg_out):
+        buf.zero_()
+    # consumed
+    m.prefetch(dtok, 1024, 512, 1)
+    assert _same(plain(1024, 512, 1), ref_a)
+    # prefetched while the previous call is still in the queue, consumed by the next one, twice in a row
+    m.prefetch(dtok, 1536, 300, 1)
+    got_b = plain(1536, 300, 1)
+    m.prefetch(dtok, 0, 100, 0)
+    got_c = plain(0, 100, 0)
+    assert _same(got_b, ref_b) and _same(got_c, ref_c)
+    # not matching (other range, other epoch): dropped
+    m.prefetch(dtok, 1536, 300, 1)
+    assert _same(plain(1024, 512, 1), ref_a)
+    m.prefetch(dtok, 1024, 512, 2)
+    assert _same(plain(1024, 512, 1), ref_a)
+    # two announcements consumed in order (the second is prepared during the first one's call); a third
+    # replaces the second
+    m.prefetch(dtok, 0, 100, 0)
+    m.prefetch(dtok, 1024, 512, 2)
+    m.prefetch(dtok, 1536, 300, 1)
+    got_c = plain(0, 100, 0)
+    got_b = plain(1536, 300, 1)
+    assert _same(got_c, ref_c) and _same(got_b, ref_b)
+    # a call for the second announcement while the first is waiting: both dropped
+    m.prefetch(dtok, 0, 100, 0)
+    m.prefetch(dtok, 1536, 300, 1)
+    assert _same(plain(1536, 300, 1), ref_b)
+    assert _same(plain(0, 100, 0), ref_c)
+    # nothing to prepare (a batch without pairs), then a normal call
+    one = torch.zeros(1, dtype=torch.int32, device="cuda")
+    m.prefetch(one, 0, 1, 0)
+    assert _same(plain(0, 100, 0), ref_c)
+    # a call that wants the negatives takes the inline path even when its batch was prefetched
+    P = m.pair_count(T, 1024, 512)
+    neg = torch.full((P * N,), -1, dtype=torch.int32, device="cuda")
+    m.prefetch(dtok, 1024, 512, 1)
+    m.sgns_grad(dtok, 1024, 512, 1, g, negatives_dbg=neg, **kw)
+    assert _same(_grad_snapshot(g, loss, seg_in, seg_out), ref_a) and int(neg.min()) >= 0
+    # the worker id enters the negatives: a prefetch made under another id is not used
+    m.prefetch(dtok, 1024, 512, 1)
+    m.rebind(m.w_in, m.w_out, 3)
+    other = plain(1024, 512, 1)
+    m.rebind(m.w_in, m.w_out, 2)
+    assert not _same(other, ref_a) and _same(plain(1024, 512, 1), ref_a)
+    # argument errors as for the gradient call
+    with pytest.raises(B.TensairError) as e:
+        m.prefetch(dtok, T - 10, 20, 0)
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.TensairError) as e:
+        m.prefetch(dtok, 0, Bc + 1, 0)
+    assert e.value.code == B.ECAPACITY
+    m.status()
+    m.close()
+
+
+@pytest.mark.parametrize("idx", [3, 5])
+def test_training_with_and_without_prefetch_is_bit_identical(idx):
+    """Several DASGD steps (peers, staleness) with the next mini-batch prefetched after every step against
+    the same steps without: own gradients, losses and final tables agree bit for bit."""
+    cfg = W.CONFIGS[idx].scaled(name=f"cfg{idx}_pf", vocab=20_000, tokens=300_000, batch=256)
+    tok, counts = W.make_stream(cfg)
+    a = DasgdWorker(cfg, tok, counts, prefetch=True)
+    b = DasgdWorker(cfg, tok, counts, prefetch=False)
+    for t in range(6):
+        a.step(want_loss=True)
+        b.step(want_loss=True)
+        assert _same(_grad_snapshot(a.own, a.mean_loss), _grad_snapshot(b.own, b.mean_loss)), f"step {t}"
+    a.model.status()
+    b.model.status()
+    for x, y in zip(a.tables_to_host(), b.tables_to_host()):
+        assert np.array_equal(x, y)
+    a.model.close()
+    b.model.close()
 
 
 # ------------------------------------------------------------------ error paths
