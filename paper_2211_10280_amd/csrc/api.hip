@@ -128,7 +128,8 @@ struct tensair_model {
     int *status;
     BatchSet set[2];
     int *long_list;
-    float *g, *center_part, *center_loss, *part_out, *part_in;
+    float *g, *center_part, *center_loss, *part_out, *part_in, *cross_out, *cross_in;
+    int *xinfo_out, *xinfo_in;
     u32 *start[2];
     u64 *mask[2];
     std::vector<uint32_t> h_thr;
@@ -205,6 +206,10 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     p = take((size_t)s.Bmax * 4); if (m) m->center_loss = (float *)p;
     p = take((size_t)s.tiles_out * 2 * D * 4); if (m) m->part_out = (float *)p;
     p = take((size_t)s.tiles_in * 2 * D * 4); if (m) m->part_in = (float *)p;
+    p = take((size_t)(s.tiles_out / TN_SEG_XBLOCK + 2) * D * 4); if (m) m->cross_out = (float *)p;
+    p = take((size_t)(s.tiles_in / TN_SEG_XBLOCK + 2) * D * 4); if (m) m->cross_in = (float *)p;
+    p = take((size_t)(s.tiles_out / TN_SEG_XBLOCK + 2) * 4); if (m) m->xinfo_out = (int *)p;
+    p = take((size_t)(s.tiles_in / TN_SEG_XBLOCK + 2) * 4); if (m) m->xinfo_in = (int *)p;
     for (int t = 0; t < 2; ++t) {
         p = take((size_t)(s.words + 1) * K1 * 4); if (m) m->start[t] = (u32 *)p;
         p = take((size_t)s.words * K1 * 8); if (m) m->mask[t] = (u64 *)p;
@@ -698,6 +703,8 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r_in.long_list = m->long_list + s.tiles_out;
     r_in.out_rows = grad_out->in.row_grads;
     r_in.part = m->part_in;
+    r_in.cross = m->cross_in;
+    r_in.xinfo = m->xinfo_in;
     r_in.mode = 1;
     r_in.center_part = m->center_part;
     r_out = r_in;
@@ -709,6 +716,8 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r_out.long_list = m->long_list;
     r_out.out_rows = grad_out->out.row_grads;
     r_out.part = m->part_out;
+    r_out.cross = m->cross_out;
+    r_out.xinfo = m->xinfo_out;
     r_out.mode = 0;
     r_out.g = m->g;
     r_out.pair_center = S.pair_center;

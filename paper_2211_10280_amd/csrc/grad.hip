@@ -223,6 +223,9 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
             e_end = (first_start < t0 && lead_long) ? tile_len : e_begin;
         }
     }
+    // first tile of a block of tiles: tell k_segcross whether a long row crosses the block's border
+    if (a.cross && (tile % TN_SEG_XBLOCK) == 0 && tile > 0 && lane == 0)
+        a.xinfo[tile / TN_SEG_XBLOCK] = (first_start < t0 && dest == 1) ? 1 : 0;
     if (e_begin >= e_end) return;
     float4 acc[ITERS];
     zero_row<ITERS>(acc);
@@ -275,7 +278,7 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
 // in-side problem costs no launch of its own and its few workgroups start first.
 struct SegReducePair {
     SegReduceArgs out, in;
-    int blocks_in;   // workgroups of the in-side problem at the front of the grid
+    int blocks_in;    // workgroups of the in-side problem at the front of the grid
 };
 
 template <typename T, int ITERS, int TILE_OUT, int TILE_IN>
@@ -305,15 +308,23 @@ __device__ __forceinline__ void segfixup_rows(const SegReduceArgs &a, int first,
         const int row = a.seg_of[t1 - 1];
         const int end = a.seg_start[row + 1];
         const int len = (end - 1) / TILE - tile;   // tiles after this one that hold a leading partial
+        // the chain: leading partials of the tiles up to the next border of a tile block, then one
+        // partial per tile block (k_segcross), the last of which ends where the row ends
+        const int b1 = tile / TN_SEG_XBLOCK + 1;
+        const int to_border = a.cross ? b1 * TN_SEG_XBLOCK - 1 - tile : len;   // no block partials: walk it all
+        const int nd = len < to_border ? len : to_border;
+        const int nc = (len > to_border) ? ((tile + len) / TN_SEG_XBLOCK - b1 + 1) : 0;
         float4 acc[ITERS];
         zero_row<ITERS>(acc);
         if (wave == 0) load_row<float, ITERS>(acc, a.part + ((size_t)tile * 2 + 1) * a.D, C4, lane);
-        for (int j0 = wave; j0 < len; j0 += NW * SEG_UNROLL) {
+        for (int j0 = wave; j0 < nd + nc; j0 += NW * SEG_UNROLL) {
             float4 r[SEG_UNROLL][ITERS];
 #pragma unroll
             for (int x = 0; x < SEG_UNROLL; ++x) {
-                int j = j0 + x * NW;
-                if (j < len) load_row<float, ITERS>(r[x], a.part + (size_t)(tile + 1 + j) * 2 * a.D, C4, lane);
+                const int j = j0 + x * NW;
+                const float *src = (j < nd) ? a.part + (size_t)(tile + 1 + j) * 2 * a.D
+                                            : a.cross + (size_t)(b1 + j - nd) * a.D;
+                if (j < nd + nc) load_row<float, ITERS>(r[x], src, C4, lane);
                 else zero_row<ITERS>(r[x]);
             }
 #pragma unroll
@@ -339,6 +350,66 @@ __device__ __forceinline__ void segfixup_rows(const SegReduceArgs &a, int first,
     }
 }
 
+// A long row's chain of partials can be very long (a hot word of a skewed stream takes a large share of
+// all entries), and one workgroup walking it alone would bound the whole step.  The tiles are therefore
+// grouped in blocks of TN_SEG_XBLOCK; at most one long row crosses the border at the start of a block,
+// and this kernel sums that row's leading partials inside the block into cross[block], all blocks in
+// parallel.  k_segfixup then adds one partial per block instead of one per tile.
+template <int ITERS, int TILE>
+__device__ __forceinline__ void segcross_block(const SegReduceArgs &a, int b, float (*red)[ITERS * WAVE * 4])
+{
+    constexpr int NW = FIXUP_THREADS / WAVE;
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
+    const int C4 = a.D >> 2;
+    const int t0 = b * TN_SEG_XBLOCK;
+    const i64 e0 = (i64)t0 * TILE;
+    if (b < 1 || e0 >= a.n || a.xinfo[b] == 0) return;
+    const int row = a.seg_of[e0];
+    const int start = a.seg_start[row];
+    const int end = a.seg_start[row + 1];
+    if (start >= e0 || end - start <= TILE) return;   // no row crosses the border, or a short one (no partials)
+    const int last_tile = (end - 1) / TILE;
+    const int cnt = (last_tile < t0 + TN_SEG_XBLOCK - 1 ? last_tile : t0 + TN_SEG_XBLOCK - 1) - t0 + 1;
+    float4 acc[ITERS];
+    zero_row<ITERS>(acc);
+    for (int j0 = wave; j0 < cnt; j0 += NW * SEG_UNROLL) {
+        float4 r[SEG_UNROLL][ITERS];
+#pragma unroll
+        for (int x = 0; x < SEG_UNROLL; ++x) {
+            int j = j0 + x * NW;
+            if (j < cnt) load_row<float, ITERS>(r[x], a.part + (size_t)(t0 + j) * 2 * a.D, C4, lane);
+            else zero_row<ITERS>(r[x]);
+        }
+#pragma unroll
+        for (int x = 0; x < SEG_UNROLL; ++x) add_row<ITERS>(acc, r[x]);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int e = (lane + WAVE * it) * 4;
+        red[wave][e + 0] = acc[it].x;
+        red[wave][e + 1] = acc[it].y;
+        red[wave][e + 2] = acc[it].z;
+        red[wave][e + 3] = acc[it].w;
+    }
+    __syncthreads();
+    float *dst = a.cross + (size_t)b * a.D;
+    for (int e = threadIdx.x; e < a.D; e += FIXUP_THREADS) {
+        float s = red[0][e];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) s += red[w][e];
+        dst[e] = s;
+    }
+}
+
+template <int ITERS, int TILE_OUT, int TILE_IN>
+__global__ void __launch_bounds__(FIXUP_THREADS) k_segcross(SegReducePair p)
+{
+    __shared__ float red[FIXUP_THREADS / WAVE][ITERS * WAVE * 4];
+    const int b = blockIdx.x;
+    if (b < p.blocks_in) segcross_block<ITERS, TILE_IN>(p.in, b, red);
+    else segcross_block<ITERS, TILE_OUT>(p.out, b - p.blocks_in, red);
+}
+
 template <int ITERS, int TILE_OUT, int TILE_IN>
 __global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReducePair p)
 {
@@ -353,10 +424,22 @@ static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
 {
     const int tiles_out = p.out.n > 0 ? (p.out.n + TILE_OUT - 1) / TILE_OUT : 0;
     const int tiles_in = p.in.n > 0 ? (p.in.n + TILE_IN - 1) / TILE_IN : 0;
+    if (tiles_out <= TN_SEG_CROSS_MIN) p.out.cross = nullptr;
+    if (tiles_in <= TN_SEG_CROSS_MIN) p.in.cross = nullptr;
     const int blocks_out = (tiles_out + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     p.blocks_in = (tiles_in + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     hipLaunchKernelGGL((k_segreduce<T, ITERS, TILE_OUT, TILE_IN>), dim3(p.blocks_in + blocks_out), dim3(BLOCK), 0,
                        st, p);
+    // Partials per block of tiles, for problems large enough that one row's chain could hold up the step:
+    // up to TN_SEG_CROSS_MIN tiles even a row that takes every entry is walked by one workgroup in well
+    // under a fifth of a millisecond, and the extra launch would cost every step several microseconds.
+    const int xb_out = tiles_out > TN_SEG_CROSS_MIN ? (tiles_out + TN_SEG_XBLOCK - 1) / TN_SEG_XBLOCK : 0;
+    const int xb_in = tiles_in > TN_SEG_CROSS_MIN ? (tiles_in + TN_SEG_XBLOCK - 1) / TN_SEG_XBLOCK : 0;
+    if (xb_out + xb_in > 0) {
+        p.blocks_in = xb_in;
+        hipLaunchKernelGGL((k_segcross<ITERS, TILE_OUT, TILE_IN>), dim3(xb_in + xb_out), dim3(FIXUP_THREADS), 0, st,
+                           p);
+    }
     // long rows exist only where a problem has more than one tile
     const int fix_out = tiles_out > 1 ? (tiles_out < 1024 ? tiles_out : 1024) : 0;
     const int fix_in = tiles_in > 1 ? (tiles_in < 1024 ? tiles_in : 1024) : 0;

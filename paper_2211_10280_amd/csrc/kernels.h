@@ -14,6 +14,8 @@ typedef int64_t i64;
 static inline int tn_seg_tile(i64 n) { return n <= 65536 ? 8 : 32; }
 #define TN_RADIX_TILE 2048  // keys per block in a radix pass (256 threads x 8)
 #define TN_SCAN_TILE 2048   // entries per block in the head scan
+#define TN_SEG_XBLOCK 256    // tiles of the segmented reduction per block of partials
+#define TN_SEG_CROSS_MIN 16384  // problems with more tiles than this get partials per block of tiles
 
 // ---- stage 0: table initialisation
 void tn_launch_init_tables(void *w_in, void *w_out, i64 V, int D, int stride, int dtype, u64 seed,
@@ -96,8 +98,11 @@ struct SegReduceArgs {
     const int *seg_start;  // first sorted entry of every row; [U] = n
     float *out_rows;       // [U][D]
     float *part;           // [ntiles][2][D] scratch for rows that cross tile borders
+    float *cross;          // [ceil(ntiles / TN_SEG_XBLOCK)][D] scratch: partials of long rows per block of tiles
+                           // (the launcher clears the pointer for problems of at most TN_SEG_CROSS_MIN tiles)
     int *long_cnt;         // [1] number of long rows found (zeroed by the segment scan)
     int *long_list;        // [ntiles] tiles in which a long row begins, in no particular order
+    int *xinfo;            // [ceil(ntiles / TN_SEG_XBLOCK)] scratch: does a long row cross the block's border
     int D;
     // source of the contribution of an entry:
     //  mode 0 (out-side): value = occurrence index o; row = g[o] * W_in[pair_center[o/(N+1)]]

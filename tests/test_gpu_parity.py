@@ -88,6 +88,7 @@ GRAD_CASES = [
     (5000, 128, 128, 40_000, 1.0, 5, 5, 1024, 2048, "bf16"),
     (2000, 512, 512, 30_000, 1.05, 5, 10, 256, 4096, "bf16"),
     (200, 256, 256, 20_000, 1.5, 8, 15, 1024, 512, "f32"),      # hot rows: segments span many tiles
+    (200, 64, 64, 40_000, 1.5, 8, 15, 2304, 512, "f32"),        # 18k tiles: hot rows chained through block partials
     (3, 64, 64, 5_000, 0.5, 3, 4, 700, 100, "f32"),             # three rows take everything
     (100_000, 1024, 1024, 30_000, 1.0, 2, 3, 64, 5, "f32"),     # widest row (4 chunk passes), 17 key bits
     (300, 4, 4, 2_000, 1.0, 1, 0, 128, 0, "f32"),               # narrowest row, no negatives
