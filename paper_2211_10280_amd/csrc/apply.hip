@@ -25,7 +25,9 @@
 #include "dev_common.h"
 #include "kernels.h"
 
+#ifndef APPLY_CHUNK
 #define APPLY_CHUNK 16   // consecutive workgroups kept on one XCD
+#endif
 
 // ---------------------------------------------------------------- index
 __global__ void __launch_bounds__(BLOCK) k_apply_clear(u64 *m0, u64 *m1, size_t n)
