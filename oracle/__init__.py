@@ -199,6 +199,35 @@ def dasgd_apply(W_in, W_out, D, dtype, grads, lr):
     dasgd_apply_table(W_out, D, dtype, [(g.gout.ids, g.gout.rows) for g in grads], lr)
 
 
+# ---------------------------------------------------------------- gradient buffer
+def grad_add_rows(a, b, D):
+    """``gradients += gradient`` of Algorithm 1 (train) for one table's sparse rows.
+
+    The buffer of gradients that have not been sent yet and a new gradient are both lists
+    of (ascending unique row ids, rows); their sum lists the union of the ids, a row that
+    only one of them has is taken over, a row that both have is added.  The buffer lives
+    in the boundary's format, float32, so every ``+=`` rounds once: the sum is taken in
+    double and rounded to float (which is the correctly rounded float sum).  A listed row
+    stays listed even if it sums to zero.  a, b: (ids int32[U], rows float32[U, D])."""
+    ia, ra = np.asarray(a[0], dtype=np.int32), np.asarray(a[1], dtype=np.float32).reshape(-1, D)
+    ib, rb = np.asarray(b[0], dtype=np.int32), np.asarray(b[1], dtype=np.float32).reshape(-1, D)
+    ids = np.union1d(ia, ib).astype(np.int32)
+    acc = np.zeros((ids.shape[0], D), dtype=np.float64)
+    acc[np.searchsorted(ids, ia)] += ra.astype(np.float64)
+    acc[np.searchsorted(ids, ib)] += rb.astype(np.float64)
+    return ids, acc.astype(np.float32)
+
+
+def grad_add(a: Grad, b: Grad, D: int) -> Grad:
+    """Sum of two sparse gradients, table by table (segment offsets and negatives do not
+    apply to a sum and are left empty)."""
+    gi = grad_add_rows((a.gin.ids, a.gin.rows), (b.gin.ids, b.gin.rows), D)
+    go = grad_add_rows((a.gout.ids, a.gout.rows), (b.gout.ids, b.gout.rows), D)
+    none = np.zeros(0, np.int64)
+    return Grad(a.P + b.P, float("nan"), np.zeros((0, 0), np.int32),
+                SparseRows(gi[0], gi[1], none), SparseRows(go[0], go[1], none))
+
+
 # ---------------------------------------------------------------- staleness
 def staleness(G_i, G_j) -> int:
     """Section 3.1: |G_i u G_j| - |G_i n G_j| for the set G_i of gradients model i had

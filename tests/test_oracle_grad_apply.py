@@ -298,3 +298,76 @@ def test_single_worker_step_is_minibatch_sgd():
     # the sparse gradient crosses the interface as float32, hence the 1e-7 relative slack
     assert np.allclose(A, W_in - lr * tA.grad.numpy(), rtol=0, atol=2e-8)
     assert np.allclose(B, W_out - lr * tB.grad.numpy(), rtol=0, atol=2e-8)
+
+
+# ------------------------------------------------------------------ gradient buffer (Algorithm 1: gradients += gradient)
+def _rand_rows(rng, V, D, U, zero_rows=0):
+    ids = np.sort(rng.choice(V, size=U, replace=False)).astype(np.int32)
+    rows = rng.standard_normal((U, D)).astype(np.float32)
+    rows[:zero_rows] = 0.0
+    return ids, rows
+
+
+def test_grad_add_is_the_dense_sum_on_the_union():
+    """Brute force: scatter both lists into a dense [V, D] table with a 'listed' flag per row."""
+    rng = np.random.default_rng(5)
+    V, D = 37, 3
+    for ua, ub in ((0, 0), (0, 5), (7, 0), (9, 11), (37, 37), (1, 1)):
+        a = _rand_rows(rng, V, D, ua, zero_rows=min(2, ua))
+        b = _rand_rows(rng, V, D, ub)
+        dense = [[0.0] * D for _ in range(V)]
+        listed = [False] * V
+        for ids, rows in (a, b):
+            for i, r in enumerate(ids):
+                listed[r] = True
+                for d in range(D):
+                    dense[r][d] += float(rows[i, d])
+        ids, rows = oracle.grad_add_rows(a, b, D)
+        want_ids = [r for r in range(V) if listed[r]]
+        assert ids.dtype == np.int32 and rows.dtype == np.float32
+        assert ids.tolist() == want_ids                      # a row listed with a zero gradient stays listed
+        for i, r in enumerate(want_ids):
+            assert rows[i].tolist() == [float(np.float32(x)) for x in dense[r]]
+
+
+def test_grad_add_identities():
+    rng = np.random.default_rng(6)
+    V, D = 500, 8
+    a, b = _rand_rows(rng, V, D, 120), _rand_rows(rng, V, D, 200)
+    empty = (np.zeros(0, np.int32), np.zeros((0, D), np.float32))
+    ids, rows = oracle.grad_add_rows(a, empty, D)
+    assert np.array_equal(ids, a[0]) and np.array_equal(rows, a[1])           # a + nothing = a
+    ab, ba = oracle.grad_add_rows(a, b, D), oracle.grad_add_rows(b, a, D)
+    assert np.array_equal(ab[0], ba[0]) and np.array_equal(ab[1], ba[1])      # commutative, bit for bit
+    assert np.array_equal(ab[0], np.union1d(a[0], b[0]))
+    both = np.intersect1d(a[0], b[0])
+    assert both.size > 0
+    r = both[0]
+    want = a[1][np.searchsorted(a[0], r)] + b[1][np.searchsorted(b[0], r)]    # float32 add is correctly rounded
+    assert np.array_equal(ab[1][np.searchsorted(ab[0], r)], want)
+    aa = oracle.grad_add_rows(a, a, D)
+    assert np.array_equal(aa[1], 2 * a[1])                                    # doubling is exact
+
+
+def test_applying_a_summed_gradient_is_applying_its_parts():
+    """Eq. 1 is linear in the gradient: one application of a + b moves the table like the merged
+    application of a and b (up to the float rounding of the sum; exactly on a dyadic grid)."""
+    rng = np.random.default_rng(7)
+    V, D = 300, 4
+    W0 = rng.standard_normal((V, D)).astype(np.float32)
+    a, b = _rand_rows(rng, V, D, 90), _rand_rows(rng, V, D, 140)
+    s = oracle.grad_add_rows(a, b, D)
+    W1, W2 = W0.copy(), W0.copy()
+    oracle.dasgd_apply_table(W1, D, oracle.F32, [s], 0.025)
+    oracle.dasgd_apply_table(W2, D, oracle.F32, [a, b], 0.025)
+    assert np.abs(W1 - W2).max() <= 2e-7 * np.abs(W0).max() and not np.array_equal(W1, W0)
+    untouched = np.setdiff1d(np.arange(V), s[0])
+    assert np.array_equal(W1[untouched], W0[untouched])
+    # dyadic grid: every product and sum is exact, so the two ways agree bit for bit
+    Wd = (rng.integers(-64, 64, (V, D)) / 8.0).astype(np.float32)
+    ad = (a[0], (rng.integers(-16, 16, a[1].shape) / 4.0).astype(np.float32))
+    bd = (b[0], (rng.integers(-16, 16, b[1].shape) / 4.0).astype(np.float32))
+    W1, W2 = Wd.copy(), Wd.copy()
+    oracle.dasgd_apply_table(W1, D, oracle.F32, [oracle.grad_add_rows(ad, bd, D)], 0.5)
+    oracle.dasgd_apply_table(W2, D, oracle.F32, [ad, bd], 0.5)
+    assert np.array_equal(W1, W2)
