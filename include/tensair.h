@@ -8,6 +8,7 @@
  *   apply_gradient(model, gradient)      -> tensair_dasgd_apply    (gradient application, Eq. 1)
  *   train(minibatch) incl. peer messages -> tensair_step
  *   a mini-batch waiting in the operator's input queue -> tensair_prefetch (optional)
+ *   gradients += gradient (the buffer sent every maxGradBuffer steps) -> tensair_grad_add
  *
  * Conventions for every call
  *   - Plain C ABI.  Pointers marked DEVICE point to GPU memory owned by the caller;
@@ -144,6 +145,19 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
  * must be strictly ascending and in range (else TENSAIR_EDATA via tensair_status). */
 int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own,
                         const tensair_sparse_grad *peers, int32_t n_peers, float lr, void *stream);
+
+/* "gradients += gradient" of Algorithm 1, train(): the sum of two sparse gradients, which is how
+ * a Model instance keeps the gradients it has computed and not yet sent (the buffer is broadcast
+ * every maxGradBuffer steps and starts again from an empty gradient, *n_rows = 0).
+ * out lists the union of the row ids of a and b, ascending; a row that only one of them has is
+ * copied, a row that both have is a's row plus b's row in fp32 (one rounding).  A listed row
+ * stays listed even if it sums to zero.  out must not share buffers with a or b.  If the union
+ * has more rows than out's capacity the result is cut off there and tensair_status reports
+ * TENSAIR_EDATA; min(vocab, a.capacity + b.capacity) always suffices.  Ids out of range or not
+ * ascending in a or b are reported the same way (such rows are skipped, nothing faults).
+ * Uses the same index scratch as tensair_dasgd_apply: calls on one model must be on one stream. */
+int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensair_sparse_grad *b,
+                     tensair_sparse_grad *out, void *stream);
 
 /* train() of Algorithm 1 for one mini-batch plus the peer gradients that arrived:
  * tensair_sgns_grad into own_out on the current tables, then tensair_dasgd_apply of

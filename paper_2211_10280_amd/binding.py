@@ -25,7 +25,7 @@ SYMBOLS = [
     "tensair_model_rebind", "tensair_model_alias", "tensair_pair_count", "tensair_sgns_grad",
     "tensair_dasgd_apply", "tensair_step", "tensair_status", "tensair_model_destroy",
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
-    "tensair_prefetch",
+    "tensair_prefetch", "tensair_grad_add",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -92,6 +92,8 @@ def lib():
         L.tensair_step.restype = C.c_int
         L.tensair_prefetch.argtypes = [vp, vp, i64, i64, i32, u32, vp]
         L.tensair_prefetch.restype = C.c_int
+        L.tensair_grad_add.argtypes = [vp, C.POINTER(SparseGrad), C.POINTER(SparseGrad), C.POINTER(SparseGrad), vp]
+        L.tensair_grad_add.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
@@ -240,6 +242,10 @@ def tensair_prefetch(h, tokens, center_begin: int, n_centers: int, epoch: int, s
                                   _stream(stream)))
 
 
+def tensair_grad_add(h, a: GradBuffers, b: GradBuffers, out: GradBuffers, stream=None):
+    _check(lib().tensair_grad_add(h, C.byref(a.c), C.byref(b.c), C.byref(out.c), _stream(stream)))
+
+
 def tensair_status(h, stream=None):
     _check(lib().tensair_status(h, _stream(stream)))
 
@@ -310,6 +316,9 @@ class Model:
 
     def step(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
         tensair_step(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+
+    def grad_add(self, a, b, out):
+        tensair_grad_add(self.h, a, b, out)
 
     def prefetch(self, tokens, begin, n, epoch):
         tensair_prefetch(self.h, tokens, begin, n, epoch)

@@ -132,6 +132,7 @@ struct tensair_model {
     int *xinfo_out, *xinfo_in;
     u32 *start[2];
     u64 *mask[2];
+    u32 *wbase[2], *wblk[2];   // tensair_grad_add: place of every 64-row word in the summed gradient
     std::vector<uint32_t> h_thr;
     std::vector<int32_t> h_alias;
     // second stream for the part of the gradient calculation that does not depend on the forward
@@ -173,7 +174,7 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     };
     const size_t V = (size_t)c.vocab, D = (size_t)c.dim;
     const size_t NE = (size_t)(s.Omax + s.Bmax);
-    const size_t K1 = (size_t)c.max_peers + 1;
+    const size_t K1 = (size_t)(c.max_peers + 1 > 2 ? c.max_peers + 1 : 2);   // the gradient sum indexes two sources
     char *p;
     p = take(V * 4); if (m) m->thr = (u32 *)p;
     p = take(V * 4); if (m) m->alias = (int *)p;
@@ -213,6 +214,8 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     for (int t = 0; t < 2; ++t) {
         p = take((size_t)(s.words + 1) * K1 * 4); if (m) m->start[t] = (u32 *)p;
         p = take((size_t)s.words * K1 * 8); if (m) m->mask[t] = (u64 *)p;
+        p = take((size_t)s.words * 4); if (m) m->wbase[t] = (u32 *)p;
+        p = take((size_t)(s.words / TN_UNION_WORDS + 1) * 4); if (m) m->wblk[t] = (u32 *)p;
     }
     return off;
 }
@@ -809,6 +812,46 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const 
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
     mark(m, PF_APPLY_UPDATE, st);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensair_sparse_grad *b,
+                     tensair_sparse_grad *out, void *stream)
+{
+    if (!m || !a || !b || !out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    const tensair_config &c = m->cfg;
+    GradSumArgs g;
+    memset(&g, 0, sizeof(g));
+    ApplyArgs &ap = g.a;
+    ap.dtype = c.dtype;
+    ap.D = c.dim;
+    ap.stride = c.row_stride;
+    ap.V = c.vocab;
+    ap.n_src = 2;
+    ap.status = m->status;
+    int rc;
+    if ((rc = fill_apply_src(ap, 0, a, "a")) || (rc = fill_apply_src(ap, 1, b, "b"))) return rc;
+    const tensair_sparse_rows *dst[2] = {&out->in, &out->out};
+    const tensair_sparse_rows *src[2][2] = {{&a->in, &b->in}, {&a->out, &b->out}};
+    for (int t = 0; t < 2; ++t) {
+        const tensair_sparse_rows &r = *dst[t];
+        if (!r.n_rows || !r.row_ids || !r.row_grads) return fail(TENSAIR_EINVAL, "out: NULL pointer");
+        if (r.capacity < 0 || r.capacity > 0x7FFFFFFFLL) return fail(TENSAIR_EINVAL, "out: bad capacity");
+        for (int k = 0; k < 2; ++k)
+            if (r.row_grads == src[t][k]->row_grads || r.row_ids == src[t][k]->row_ids ||
+                r.n_rows == src[t][k]->n_rows)
+                return fail(TENSAIR_EINVAL, "out must not share buffers with a or b");
+        ap.start[t] = m->start[t];
+        ap.mask[t] = m->mask[t];
+        g.out_ids[t] = r.row_ids;
+        g.out_rows[t] = r.row_grads;
+        g.out_n[t] = r.n_rows;
+        g.out_cap[t] = r.capacity;
+        g.wbase[t] = m->wbase[t];
+        g.wblk[t] = m->wblk[t];
+    }
+    tn_launch_grad_sum(g, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }

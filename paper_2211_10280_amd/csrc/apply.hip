@@ -260,3 +260,184 @@ void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st)
     if (a.dtype == 0) launch_apply_t<float>(a, st);
     else launch_apply_t<bf16_t>(a, st);
 }
+
+// ---------------------------------------------------------------- sum of sparse gradients
+// Algorithm 1 keeps the gradients a Model instance has computed and not yet sent in a buffer
+// ("gradients += gradient") and broadcasts the buffer every maxGradBuffer steps.  In the sparse form
+// that sum lists the union of the rows: a row one source has is taken over, a row several have is
+// added in source order (fp32, one rounding per addition).  The same per-word index as for the table
+// update tells where every source's rows are; a scan over the popcounts of the united masks gives each
+// 64-row word its place in the output, so ids come out ascending without any sort or merge.
+#define UNION_WPT (TN_UNION_WORDS / BLOCK)
+
+__device__ __forceinline__ u64 united_mask(const u64 *mask, size_t word, int ns)
+{
+    u64 u = 0;
+    for (int k = 0; k < ns; ++k) u |= mask[word * ns + k];
+    return u;
+}
+
+// block-wide exclusive scan of one int per thread; total = block total
+__device__ __forceinline__ int block_scan1(int x, int &total, int *sm)
+{
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int incl = (int)wave_incl_scan((u32)x, lane);
+    if (lane == WAVE - 1) sm[wave] = incl;
+    __syncthreads();
+    int off = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES_PER_BLOCK; ++w) {
+        if (w < wave) off += sm[w];
+        total += sm[w];
+    }
+    __syncthreads();
+    return off + incl - x;
+}
+
+// grid (blocks, 2 tables): rows of the union inside each block of TN_UNION_WORDS words
+__global__ void __launch_bounds__(BLOCK) k_union_count(GradSumArgs g)
+{
+    __shared__ int sm[WAVES_PER_BLOCK];
+    const int tb = blockIdx.y, ns = g.a.n_src;
+    const size_t words = (size_t)((g.a.V + 63) >> 6);
+    const size_t w0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * UNION_WPT;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < UNION_WPT; ++j)
+        if (w0 + j < words) cnt += __popcll(united_mask(g.a.mask[tb], w0 + j, ns));
+    int total;
+    block_scan1(cnt, total, sm);
+    if (threadIdx.x == 0) g.wblk[tb][blockIdx.x] = (u32)total;
+}
+
+// grid (blocks, 2 tables): place of every word in the output; the last block writes the row count
+__global__ void __launch_bounds__(BLOCK) k_union_offsets(GradSumArgs g)
+{
+    __shared__ int sm[WAVES_PER_BLOCK];
+    const int tb = blockIdx.y, ns = g.a.n_src;
+    const size_t words = (size_t)((g.a.V + 63) >> 6);
+    int before = 0;
+    for (int j = threadIdx.x; j < (int)blockIdx.x; j += BLOCK) before += (int)g.wblk[tb][j];
+    int prefix;
+    block_scan1(before, prefix, sm);   // prefix = rows of the union in all earlier blocks
+    const size_t w0 = ((size_t)blockIdx.x * BLOCK + threadIdx.x) * UNION_WPT;
+    int c[UNION_WPT];
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < UNION_WPT; ++j) {
+        c[j] = (w0 + j < words) ? __popcll(united_mask(g.a.mask[tb], w0 + j, ns)) : 0;
+        cnt += c[j];
+    }
+    int total;
+    int run = prefix + block_scan1(cnt, total, sm);
+#pragma unroll
+    for (int j = 0; j < UNION_WPT; ++j) {
+        if (w0 + j < words) g.wbase[tb][w0 + j] = (u32)run;
+        run += c[j];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        i64 U = (i64)prefix + total;
+        if (U > g.out_cap[tb]) {
+            U = g.out_cap[tb];
+            atomicOr(g.a.status, ST_OVERFLOW);
+        }
+        *g.out_n[tb] = (int)U;
+    }
+}
+
+// one wave per G consecutive vocabulary rows of both tables, as in k_apply
+template <int ITERS, int G>
+__global__ void __launch_bounds__(BLOCK) k_grad_sum(GradSumArgs g, int nblocks)
+{
+    const ApplyArgs &a = g.a;
+    constexpr int GPW = 64 / G;
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
+    const int gw = blockIdx.x * WAVES_PER_BLOCK + wave;
+    const int word = gw / GPW, sub = gw - word * GPW;
+    const int words = (int)((a.V + 63) >> 6);
+    if (word >= words) return;
+    const int ns = a.n_src;
+    const int C4 = a.D >> 2;
+    const int lo = sub * G;
+
+    u64 mk = 0;
+    u32 st = 0;
+    int U = 0;
+    u64 rows_ptr = 0;
+    {
+        const int tb = lane >> 5, k = lane & 31;
+        if (k < ns) {
+            const ApplySrc &s = a.src[tb][k];
+            if (s.ids != nullptr) {
+                mk = a.mask[tb][(size_t)word * ns + k];
+                st = a.start[tb][(size_t)word * ns + k];
+                U = *s.n_rows;
+                if ((i64)U > s.capacity) U = (int)s.capacity;
+                rows_ptr = (u64)s.rows;
+            }
+        }
+    }
+    const i64 row0 = (i64)word * 64;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const bool mine = (lane >> 5) == tb;
+        // rows of the word that any source has
+        const u32 ulo = (u32)uniform((int)wave_or(mine ? (u32)mk : 0u));
+        const u32 uhi = (u32)uniform((int)wave_or(mine ? (u32)(mk >> 32) : 0u));
+        const u64 uw = ((u64)uhi << 32) | ulo;
+        u64 um = (G == 64) ? uw : ((uw >> lo) & ((1ull << (G & 63)) - 1ull));
+        const u32 base = g.wbase[tb][word];
+        while (um) {
+            const int b = lo + (int)__builtin_ctzll(um);
+            um &= um - 1ull;
+            const i64 r = row0 + b;
+            const i64 dst = (i64)base + __popcll(uw & ((1ull << b) - 1ull));
+            if (r >= a.V || dst >= g.out_cap[tb]) break;   // corrupt index or overflow (both flagged)
+            const u32 pos = st + (u32)__popcll(mk & ((1ull << b) - 1ull));
+            const bool ok = mine && ((mk >> b) & 1ull) && (pos < (u32)U);
+            u64 S = __ballot(ok);
+            float4 acc[ITERS];
+            zero_row<ITERS>(acc);
+            while (S) {
+                float4 x[4][ITERS];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (S) {
+                        const int k = (int)__builtin_ctzll(S);
+                        S &= S - 1ull;
+                        const float *src = (const float *)rd_lane64(rows_ptr, k) + (size_t)(u32)rd_lane((int)pos, k) * a.D;
+                        load_row<float, ITERS>(x[j], src, C4, lane);
+                    } else {
+                        zero_row<ITERS>(x[j]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) add_row<ITERS>(acc, x[j]);
+            }
+            store_row<float, ITERS>(g.out_rows[tb] + (size_t)dst * a.D, acc, C4, lane);
+            if (lane == 0) g.out_ids[tb][dst] = (int)r;
+        }
+    }
+}
+
+void tn_launch_grad_sum(const GradSumArgs &g, hipStream_t st)
+{
+    const ApplyArgs &a = g.a;
+    tn_launch_apply_clear(a, st);
+    tn_launch_apply_index(a, 0, a.n_src, st);
+    const int words = (int)((a.V + 63) >> 6);
+    const int sblocks = (words + TN_UNION_WORDS - 1) / TN_UNION_WORDS;
+    hipLaunchKernelGGL(k_union_count, dim3(sblocks, 2), dim3(BLOCK), 0, st, g);
+    hipLaunchKernelGGL(k_union_offsets, dim3(sblocks, 2), dim3(BLOCK), 0, st, g);
+    const int iters = (a.D / 4 + WAVE - 1) / WAVE;
+    const i64 nwaves = (i64)words * (64 / APPLY_G);
+    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    dim3 grid(nblocks), blk(BLOCK);
+    switch (iters) {
+    case 1: hipLaunchKernelGGL((k_grad_sum<1, APPLY_G>), grid, blk, 0, st, g, nblocks); break;
+    case 2: hipLaunchKernelGGL((k_grad_sum<2, APPLY_G>), grid, blk, 0, st, g, nblocks); break;
+    case 3: hipLaunchKernelGGL((k_grad_sum<3, APPLY_G>), grid, blk, 0, st, g, nblocks); break;
+    default: hipLaunchKernelGGL((k_grad_sum<4, APPLY_G>), grid, blk, 0, st, g, nblocks); break;
+    }
+}

@@ -145,5 +145,18 @@ void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st);
 void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st);
 void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st);
 
+// ---- sum of sparse gradients: out = src_0 + src_1 + ... on the union of their rows
+struct GradSumArgs {
+    ApplyArgs a;             // sources, index arrays, V, D (tables, lr unused)
+    int *out_ids[2];         // [capacity] ascending
+    float *out_rows[2];      // [capacity][D]
+    int *out_n[2];           // [1]
+    i64 out_cap[2];
+    u32 *wbase[2];           // [words] scratch: rows of the union before each 64-row word
+    u32 *wblk[2];            // [ceil(words / TN_UNION_WORDS)] scratch: rows of the union per block of words
+};
+#define TN_UNION_WORDS 1024  // vocabulary words per workgroup in the union scan (256 threads x 4)
+void tn_launch_grad_sum(const GradSumArgs &g, hipStream_t st);
+
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)
 void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);

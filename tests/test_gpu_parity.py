@@ -343,6 +343,84 @@ def test_train_full_size_configs(idx, steps):
     _run_both(W.CONFIGS[idx], steps)
 
 
+# ------------------------------------------------------------------ gradient buffer (gradients += gradient)
+def _load_grad(m, rng, V, D, ui, uo, cap_pad=3):
+    gi, go = _rand_sparse(rng, V, D, ui), _rand_sparse(rng, V, D, uo)
+    buf = B.GradBuffers(ui + cap_pad, uo + cap_pad, D)
+    buf.load(gi[0], gi[1], go[0], go[1])
+    return buf, gi, go
+
+
+@pytest.mark.parametrize("V,D,ua,ub", [(1000, 32, (40, 300), (25, 500)),      # overlapping
+                                        (4099, 300, (0, 0), (17, 2100)),       # empty buffer + gradient (first +=)
+                                        (4099, 300, (300, 4099), (299, 4099)), # every row of W_out in both
+                                        (70, 1024, (1, 33), (69, 2)),          # widest row, V not a multiple of 64
+                                        (200_000, 8, (5000, 120_000), (7000, 90_000))])   # several scan blocks
+def test_grad_add_parity(V, D, ua, ub):
+    _say("grad_add", V, D, ua, ub)
+    rng = np.random.default_rng(V + D)
+    m = B.Model(V, D, B.F32, 2, 3, 16, 0, 1, np.ones(V, np.uint64))
+    a, a_in, a_out = _load_grad(m, rng, V, D, *ua)
+    b, b_in, b_out = _load_grad(m, rng, V, D, *ub)
+    out = B.GradBuffers(min(V, ua[0] + ub[0]) + 1, min(V, ua[1] + ub[1]) + 1, D)
+    out.in_rows.fill_(float("nan"))
+    out.out_rows.fill_(float("nan"))
+    m.grad_add(a, b, out)
+    m.status()
+    (ids_in, rows_in), (ids_out, rows_out) = out.to_host()
+    w_in = oracle.grad_add_rows(a_in, b_in, D)
+    w_out = oracle.grad_add_rows(a_out, b_out, D)
+    assert np.array_equal(ids_in, w_in[0]) and np.array_equal(ids_out, w_out[0])
+    # one float addition per element, correctly rounded on both sides: bit-exact
+    assert np.array_equal(rows_in, w_in[1]) and np.array_equal(rows_out, w_out[1])
+    # the inputs are read-only
+    assert np.array_equal(a.out_rows[: ua[1]].cpu().numpy(), a_out[1]) and a.sizes() == ua
+    m.close()
+
+
+def test_grad_add_of_real_gradients_and_errors():
+    cfg = W.CONFIGS[3].scaled(name="cfg3_add", vocab=20_000, tokens=300_000, batch=256)
+    tok, counts = W.make_stream(cfg)
+    m = B.Model(cfg.vocab, cfg.dim, B.F32, cfg.window, cfg.negatives, cfg.batch, 1, cfg.seed, counts)
+    dtok = torch.from_numpy(tok).cuda()
+    g1, g2 = m.grad_buffers(), m.grad_buffers()
+    # a table with non-zero W_out so that both sides of the gradient are non-trivial
+    m.w_out.copy_(torch.from_numpy(_random_tables(cfg.vocab, cfg.dim, cfg.dim, "f32", 3)[1]).cuda())
+    m.sgns_grad(dtok, 0, 256, 0, g1)
+    m.sgns_grad(dtok, 256, 256, 0, g2)
+    acc = B.GradBuffers(min(cfg.vocab, 2 * g1.cap_in), min(cfg.vocab, 2 * g1.cap_out), cfg.dim)
+    m.grad_add(g1, g2, acc)
+    m.status()
+    (i1, r1), (o1, q1) = g1.to_host()
+    (i2, r2), (o2, q2) = g2.to_host()
+    (ia, ra), (oa, qa) = acc.to_host()
+    wi, wo = oracle.grad_add_rows((i1, r1), (i2, r2), cfg.dim), oracle.grad_add_rows((o1, q1), (o2, q2), cfg.dim)
+    assert np.array_equal(ia, wi[0]) and np.array_equal(oa, wo[0])
+    assert np.array_equal(ra, wi[1]) and np.array_equal(qa, wo[1])
+    assert ia.size < i1.size + i2.size and oa.size < o1.size + o2.size          # rows in common were merged
+    # applying the sum = applying the parts in one merged update (Eq. 1 is linear), to float rounding
+    w0_in, w0_out = m.w_in.clone(), m.w_out.clone()
+    m.dasgd_apply(acc, [], 0.025)
+    s_in, s_out = m.w_in.clone(), m.w_out.clone()
+    m.w_in.copy_(w0_in)
+    m.w_out.copy_(w0_out)
+    m.dasgd_apply(g1, [g2], 0.025)
+    assert (s_out - m.w_out).abs().max().item() <= 2e-7 * w0_out.abs().max().item()
+    assert (s_in - m.w_in).abs().max().item() <= 2e-7 * w0_in.abs().max().item()
+    # errors: shared buffers are refused; an output that is too small is cut off and reported
+    with pytest.raises(B.TensairError) as e:
+        m.grad_add(g1, g2, g1)
+    assert e.value.code == B.EINVAL
+    small = B.GradBuffers(4, 4, cfg.dim)
+    m.grad_add(g1, g2, small)
+    with pytest.raises(B.TensairError) as e:
+        m.status()
+    assert e.value.code == B.EDATA and small.sizes() == (4, 4)
+    assert np.array_equal(small.out_ids.cpu().numpy(), wo[0][:4])
+    m.status()
+    m.close()
+
+
 # ------------------------------------------------------------------ prefetch of the coming mini-batch
 def _grad_snapshot(g, loss=None, seg_in=None, seg_out=None):
     ui, uo = g.sizes()
