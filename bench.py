@@ -50,6 +50,8 @@ def main():
                     help="every step self-contained (default: the next mini-batch is handed to tensair_prefetch "
                          "after each step, as it would be waiting in the worker's input queue)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
+    ap.add_argument("--op", choices=["step", "grad_add"], default="step",
+                    help="step: the worker step (the metric); grad_add: the gradient-buffer sum on its own")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU worker step; there is no multi-GPU path (--gpus must be 1)")
@@ -72,6 +74,9 @@ def main():
     t0 = time.perf_counter()
     tok, counts = W.make_stream(cfg)
     log(f"[bench] workload {cfg.name}: stream of {cfg.tokens} tokens in {time.perf_counter() - t0:.1f}s")
+
+    if args.op == "grad_add":
+        return bench_grad_add(args, cfg, tok, counts)
 
     worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch)
     model = worker.model
@@ -226,6 +231,76 @@ def main():
                                          f"untimed, as on the GPU",
                                "host_cpus": os.cpu_count()}
     print(json.dumps(out), flush=True)
+
+
+def bench_grad_add(args, cfg, tok, counts):
+    """gradients += gradient on two consecutive own gradients of the workload (first sum of a window)."""
+    import numpy as np
+    import torch
+
+    from paper_2211_10280_amd import binding as B
+    from paper_2211_10280_amd import workload as W
+
+    dt = B.F32 if cfg.dtype == "f32" else B.BF16
+    m = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch, max(cfg.peers, 1), cfg.seed, counts)
+    dtok = torch.from_numpy(np.ascontiguousarray(tok, dtype=np.int32)).cuda()
+    # W_out away from zero so that both sides carry non-trivial rows (values do not change the traffic)
+    m.w_out.copy_(m.w_in)
+    g1, g2 = m.grad_buffers(), m.grad_buffers()
+    b1, b2 = W.worker_batch(cfg, 0, 0), W.worker_batch(cfg, 1, 0)
+    m.sgns_grad(dtok, b1[0], b1[1], b1[2], g1)
+    m.sgns_grad(dtok, b2[0], b2[1], b2[2], g2)
+    out = B.GradBuffers(min(cfg.vocab, 2 * g1.cap_in), min(cfg.vocab, 2 * g1.cap_out), cfg.dim)
+    S = args.steps if args.steps else 50
+    Wm = args.warmup if args.warmup is not None else 5
+    for _ in range(Wm):
+        m.grad_add(g1, g2, out)
+    B.tensair_profile(m.h, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(S):
+        m.grad_add(g1, g2, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    recs = B.tensair_profile_read(m.h)
+    B.tensair_profile(m.h, 0)
+    m.status()
+    rows_ms = [ms for tag, ms in recs if tag == "add_rows"]
+    assert len(rows_ms) == S
+    (ua_in, ua_out), (ub_in, ub_out), (uo_in, uo_out) = g1.sizes(), g2.sizes(), out.sizes()
+    D = cfg.dim
+    # algorithmic bytes of one sum: read both gradients' rows, write the union's rows, ids read and written
+    bytes_rows = (ua_in + ua_out + ub_in + ub_out + uo_in + uo_out) * D * 4
+    bytes_ids = (ua_in + ua_out + ub_in + ub_out + uo_in + uo_out) * 4
+    alg = bytes_rows + bytes_ids
+    k_s = sum(rows_ms) / S * 1e-3
+    out_json = {
+        "metric": "gradient buffer accumulation (gradients += gradient): rows of the sum per second",
+        "value": (uo_in + uo_out) / (elapsed / S), "unit": "rows/s", "n_gpus": 1, "steps": S, "warmup": Wm,
+        "ms_per_step": elapsed / S * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name + ":grad_add", "rows_a": ua_in + ua_out, "rows_b": ub_in + ub_out,
+                   "rows_sum": uo_in + uo_out, "dim": D},
+        "roofline": {"bound": "hbm", "kernel": "k_grad_sum", "achieved": bytes_rows / k_s / 1e9,
+                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": bytes_rows / k_s / HBM_PEAK, "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_rows, "avg_launch_ms": k_s * 1e3,
+                     "whole_call_algorithmic_bytes": alg, "whole_call_frac": alg / (elapsed / S) / HBM_PEAK},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+
+        (i1, r1), (o1, q1) = g1.to_host()
+        (i2, r2), (o2, q2) = g2.to_host()
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            oracle.grad_add_rows((i1, r1), (i2, r2), D)
+            oracle.grad_add_rows((o1, q1), (o2, q2), D)
+            reps += 1
+        cpu_t = (time.perf_counter() - t0) / reps
+        out_json["cpu_baseline"] = {"value": (uo_in + uo_out) / cpu_t, "unit": "rows/s", "cores": 1, "kind": "oracle",
+                                    "sample": f"{reps} sums of the same two gradients ({cpu_t:.3f} s each)"}
+    print(json.dumps(out_json), flush=True)
 
 
 if __name__ == "__main__":

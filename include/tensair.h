@@ -199,8 +199,9 @@ int tensair_status(tensair_model *m, void *stream);
  * tensair_profile_read waits for the last recorded event, writes up to max_records
  * (tag, milliseconds) records since the previous read and returns their number (negative =
  * error).  Tags: 1 keys+negatives, 2 forward, 3 sort, 4 segments, 5 reduce W_in side,
- * 6 reduce W_out side, 8 apply index, 9 apply table update; a tag's time runs from the
- * previous event to its own.  At most 65536 events are kept between reads. */
+ * 6 reduce W_out side, 8 apply index, 9 apply table update, 11 index and scan of
+ * tensair_grad_add, 12 its row kernel (level 1 also brackets that one); a tag's time runs from
+ * the previous event to its own.  At most 65536 events are kept between reads. */
 int tensair_profile(tensair_model *m, int level);
 int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max_records);
 

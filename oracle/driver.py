@@ -5,7 +5,12 @@ ordering of Section 3.1 of TensAIR (arXiv 2211.10280): at step t the worker
 computes its own gradient on theta_t, then applies it together with the K
 gradients that arrived; peer k's gradient was computed on the peer's own
 mini-batch against theta_{max(0, t - s)}, s being that gradient's staleness
-counted in this worker's steps.
+counted in this worker's steps.  With maxGradBuffer = n > 1 every instance sums
+its gradients ("gradients += gradient") and broadcasts the sum after every n-th of
+its steps: the K peer buffers then arrive together at this worker's steps n-1,
+2n-1, ..., each holding that peer's gradients of the last n steps (every one
+computed when its step took place, on the snapshot its staleness names), and no
+peer gradient is applied at the steps in between.
 """
 from __future__ import annotations
 
@@ -33,6 +38,10 @@ class OracleWorker:
         self.last_peers = []
         # G sets of Section 3.1: gradients this worker has applied, as (step, worker) names
         self.applied = set()
+        # maxGradBuffer: the sums not yet broadcast (None = empty), this worker's and the peers'
+        self.own_buffer = None
+        self.peer_buffers = [None] * cfg.peers
+        self.sent = None             # the buffer this worker broadcast most recently
 
     def _grad(self, W_in, W_out, begin, n, epoch, worker):
         c = self.cfg
@@ -67,6 +76,18 @@ class OracleWorker:
             grads = [self._grad(*jobs[0])]
             self.t_own = time.perf_counter() - t0            # the worker's own calculate_gradient
             grads += [self._grad(*j) for j in jobs[1:]]      # what the other instances would have sent
+        n = c.grad_buffer
+        if n > 1:
+            # gradients += gradient, for this worker and for every peer; what arrives at this step
+            add = lambda buf, g: g if buf is None else oracle.grad_add(buf, g, c.dim)
+            self.own_buffer = add(self.own_buffer, grads[0])
+            self.peer_buffers = [add(b, g) for b, g in zip(self.peer_buffers, grads[1:])]
+            arrive = (t + 1) % n == 0
+            grads = [grads[0]] + (self.peer_buffers if arrive else [])
+            if arrive:
+                self.sent = self.own_buffer
+                self.own_buffer = None
+                self.peer_buffers = [None] * c.peers
         t0 = time.perf_counter()
         oracle.dasgd_apply(self.W_in, self.W_out, c.dim, self.dtype, grads, c.lr)
         self.t_apply = time.perf_counter() - t0

@@ -29,7 +29,7 @@ SYMBOLS = [
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
-                8: "apply_index", 9: "apply_update"}
+                8: "apply_index", 9: "apply_update", 11: "add_index", 12: "add_rows"}
 
 
 class TensairError(RuntimeError):

@@ -265,12 +265,14 @@ bool build_alias(const uint64_t *counts, i64 V, std::vector<uint32_t> &thr,
 
 // Stage tags of tensair_profile_read.  A tag's duration runs from the previous mark to its own.
 enum { PF_BEGIN_GRAD = 0, PF_KEYS, PF_FORWARD, PF_SORT, PF_SEGMENTS, PF_REDUCE_IN, PF_REDUCE_OUT,
-       PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE };
+       PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE, PF_BEGIN_ADD, PF_ADD_INDEX, PF_ADD_ROWS };
 
 void mark(tensair_model *m, int tag, hipStream_t st)
 {
     if (m->prof_level == 0) return;
-    if (m->prof_level == 1 && tag != PF_APPLY_INDEX && tag != PF_APPLY_UPDATE) return;
+    if (m->prof_level == 1 && tag != PF_APPLY_INDEX && tag != PF_APPLY_UPDATE && tag != PF_ADD_INDEX &&
+        tag != PF_ADD_ROWS)
+        return;
     if (m->prof_marks.size() >= 65536) return;
     hipEvent_t ev;
     if (m->prof_used < m->prof_pool.size()) {
@@ -851,7 +853,12 @@ int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensa
         g.wbase[t] = m->wbase[t];
         g.wblk[t] = m->wblk[t];
     }
-    tn_launch_grad_sum(g, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    mark(m, PF_BEGIN_ADD, st);
+    tn_launch_grad_sum_index(g, st);
+    mark(m, PF_ADD_INDEX, st);
+    tn_launch_grad_sum_rows(g, st);
+    mark(m, PF_ADD_ROWS, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }
@@ -940,8 +947,8 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
     }
     for (size_t i = 1; i < m->prof_marks.size() && n < max_records; ++i) {
         const int tag = m->prof_marks[i].first;
-        if (tag == PF_BEGIN_GRAD || tag == PF_BEGIN_APPLY) continue;
-        if (m->prof_level == 1 && tag != PF_APPLY_UPDATE) continue;
+        if (tag == PF_BEGIN_GRAD || tag == PF_BEGIN_APPLY || tag == PF_BEGIN_ADD) continue;
+        if (m->prof_level == 1 && tag != PF_APPLY_UPDATE && tag != PF_ADD_ROWS) continue;
         float t = 0.f;
         if (hipEventElapsedTime(&t, m->prof_marks[i - 1].second, m->prof_marks[i].second) != hipSuccess) continue;
         tags[n] = tag;

@@ -421,7 +421,8 @@ __global__ void __launch_bounds__(BLOCK) k_grad_sum(GradSumArgs g, int nblocks)
     }
 }
 
-void tn_launch_grad_sum(const GradSumArgs &g, hipStream_t st)
+// index of the sources and place of every word in the output
+void tn_launch_grad_sum_index(const GradSumArgs &g, hipStream_t st)
 {
     const ApplyArgs &a = g.a;
     tn_launch_apply_clear(a, st);
@@ -430,6 +431,12 @@ void tn_launch_grad_sum(const GradSumArgs &g, hipStream_t st)
     const int sblocks = (words + TN_UNION_WORDS - 1) / TN_UNION_WORDS;
     hipLaunchKernelGGL(k_union_count, dim3(sblocks, 2), dim3(BLOCK), 0, st, g);
     hipLaunchKernelGGL(k_union_offsets, dim3(sblocks, 2), dim3(BLOCK), 0, st, g);
+}
+
+void tn_launch_grad_sum_rows(const GradSumArgs &g, hipStream_t st)
+{
+    const ApplyArgs &a = g.a;
+    const int words = (int)((a.V + 63) >> 6);
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     const i64 nwaves = (i64)words * (64 / APPLY_G);
     const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);

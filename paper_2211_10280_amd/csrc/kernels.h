@@ -156,7 +156,8 @@ struct GradSumArgs {
     u32 *wblk[2];            // [ceil(words / TN_UNION_WORDS)] scratch: rows of the union per block of words
 };
 #define TN_UNION_WORDS 1024  // vocabulary words per workgroup in the union scan (256 threads x 4)
-void tn_launch_grad_sum(const GradSumArgs &g, hipStream_t st);
+void tn_launch_grad_sum_index(const GradSumArgs &g, hipStream_t st);   // index + scan
+void tn_launch_grad_sum_rows(const GradSumArgs &g, hipStream_t st);    // the rows themselves
 
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)
 void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);

@@ -7,6 +7,9 @@ the other instances "arrive".  With one GPU there are no other instances, so
 their gradients are produced here with ``tensair_sgns_grad`` on the peers' own
 mini-batches against a snapshot of this worker's model that is 0..max_stale
 steps old (the staleness of Section 3.1, counted in this worker's steps).
+With maxGradBuffer = n > 1 (Algorithm 1) every instance sums its gradients with
+``tensair_grad_add`` and sends the sum after every n-th step, so the K peer
+buffers arrive together at steps n-1, 2n-1, ... and none in between.
 Everything numerical happens inside the library; this file only sequences calls
 and keeps buffers.
 """
@@ -41,6 +44,14 @@ class DasgdWorker:
         self.mean_loss = torch.zeros(1, dtype=torch.float32, device=device)
         self.step_no = 0
         self.stale = None
+        # maxGradBuffer > 1: sums not yet sent, two buffers each (tensair_grad_add writes a third operand)
+        self.sent = None
+        if cfg.grad_buffer > 1:
+            n = cfg.grad_buffer
+            big = lambda: B.GradBuffers(min(cfg.vocab, n * self.own.cap_in), min(cfg.vocab, n * self.own.cap_out),
+                                        cfg.dim, device)
+            self.own_acc = [big(), big()]
+            self.peer_acc = [[big(), big()] for _ in range(cfg.peers)]
 
     # -- peers -------------------------------------------------------------
     def _snapshot(self, t):
@@ -65,7 +76,22 @@ class DasgdWorker:
             begin, n, epoch = W.worker_batch(cfg, t, k)
             self.peer_model.rebind(w_in, w_out, k)
             self.peer_model.sgns_grad(self.tokens, begin, n, epoch, self.peer_bufs[k - 1])
+        if cfg.grad_buffer > 1:
+            return self._buffer_peers(t)
         return self.peer_bufs
+
+    def _accumulate(self, pair, g, first):
+        """pair[0] <- pair[0] + g (gradients += gradient); an empty sum at the start of a window."""
+        if first:
+            pair[0].n_rows.zero_()
+        self.model.grad_add(pair[0], g, pair[1])
+        pair[0], pair[1] = pair[1], pair[0]
+
+    def _buffer_peers(self, t):
+        n = self.cfg.grad_buffer
+        for k in range(self.cfg.peers):
+            self._accumulate(self.peer_acc[k], self.peer_bufs[k], t % n == 0)
+        return [p[0] for p in self.peer_acc] if (t + 1) % n == 0 else []
 
     # -- one step -----------------------------------------------------------
     def step(self, peers=None, want_loss=False):
@@ -82,6 +108,10 @@ class DasgdWorker:
             self._announce(t + 1)
         self.model.step(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
                         self.mean_loss if want_loss else None)
+        if cfg.grad_buffer > 1:
+            self._accumulate(self.own_acc, self.own, t % cfg.grad_buffer == 0)
+            if (t + 1) % cfg.grad_buffer == 0:
+                self.sent = self.own_acc[0]      # what this worker would broadcast now
         self.step_no += 1
         if self.prefetch and self.announced < t + 1:
             self._announce(t + 1)

@@ -39,6 +39,7 @@ class Config:
     max_stale: int      # peer snapshots are 0..max_stale steps old
     lr: float           # alpha of Eq. 1
     parity_steps: int   # steps the multi-step parity runs use
+    grad_buffer: int = 1   # maxGradBuffer of Algorithm 1: own gradients summed per broadcast
 
     # seeds: one per purpose so that changing one input does not move another
     @property

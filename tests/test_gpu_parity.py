@@ -288,11 +288,17 @@ def _run_both(cfg, steps, threads=8, prefetch=True):
         worst_rows = max(worst_rows, e)
         assert abs(gw.mean_loss.item() - og.loss) <= TOL_LOSS * og.loss, f"step {t}"
         # peers: ids bit-exact as well (they were computed on the GPU from the GPU's own snapshots)
+        peer_side = gw.peer_bufs if cfg.grad_buffer == 1 else [p[0] for p in gw.peer_acc]
         for k, pg in enumerate(grads[1:]):
-            ui, uo = gw.peer_bufs[k].sizes()
+            ui, uo = peer_side[k].sizes()
             assert ui == pg.gin.ids.size and uo == pg.gout.ids.size, f"step {t} peer {k + 1}"
         if cfg.peers and cfg.max_stale:
             assert all(s % (cfg.peers + 1) == 0 for s in ow.last_staleness)
+        if cfg.grad_buffer > 1 and (t + 1) % cfg.grad_buffer == 0:
+            # the buffer this worker broadcasts: the sum of its last grad_buffer gradients
+            (bi, br), (bo, bq) = gw.sent.to_host()
+            assert np.array_equal(bi, ow.sent.gin.ids) and np.array_equal(bo, ow.sent.gout.ids), f"step {t}"
+            worst_rows = max(worst_rows, rows_rel(br, ow.sent.gin.rows), rows_rel(bq, ow.sent.gout.rows))
     gw.model.status()
     g_in, g_out = gw.tables_to_host()
     _say(f"   {cfg.name}: {steps} steps, worst own-gradient row error {worst_rows:.2e}")
@@ -334,6 +340,15 @@ def test_train_scaled_configs(name, kw, steps, prefetch):
     base = W.CONFIGS[int(name[3])]
     _say("train", name, "prefetch" if prefetch else "inline")
     _run_both(base.scaled(name=name, **kw), steps, prefetch=prefetch)
+
+
+@pytest.mark.parametrize("idx,n,steps", [(2, 2, 9), (3, 3, 7), (5, 2, 5)])
+def test_train_with_gradient_buffer(idx, n, steps):
+    """maxGradBuffer = n of Algorithm 1: every instance sums n gradients per broadcast, so the peers' sums
+    arrive at every n-th step; tables, own gradients and the broadcast buffers against the oracle."""
+    cfg = W.CONFIGS[idx].scaled(name=f"cfg{idx}_buf{n}", vocab=20_000, tokens=300_000, batch=256, grad_buffer=n)
+    _say("train with gradient buffer", cfg.name)
+    _run_both(cfg, steps)
 
 
 @pytest.mark.parametrize("idx,steps", [(2, 6), (3, 5), (4, 2), (5, 2)])
