@@ -228,6 +228,70 @@ def grad_add(a: Grad, b: Grad, D: int) -> Grad:
                 SparseRows(gi[0], gi[1], none), SparseRows(go[0], go[1], none))
 
 
+# ---------------------------------------------------------------- dense model, predict path, drift metric
+def dense_apply(theta, dtype, grads, lr):
+    """apply_gradient of Algorithm 1 / Eq. 1 for a dense model (Section 4, "Sparse vs. Dense
+    Models": every variable receives gradient), in place: theta <- theta - alpha * sum_k g_k
+    for the own gradient and the gradients received from peers, summed in double, one rounded
+    store per element.  theta: 1-D array in its own type (float32, or uint16 bfloat16 bits);
+    grads: list of float32 arrays of the same length; alpha enters as (double)(float)lr."""
+    assert theta.ndim == 1 and theta.dtype == _NP[dtype]
+    acc = np.zeros(theta.shape[0], dtype=np.float64)
+    for g in grads:
+        g = np.asarray(g, dtype=np.float32)
+        assert g.shape == theta.shape
+        acc += g.astype(np.float64)
+    alpha = float(np.float32(lr))
+    if dtype == BF16:
+        new = bf16_to_f32(theta).astype(np.float64) - alpha * acc
+        theta[:] = _bf16_round(new)
+    else:
+        theta[:] = (theta.astype(np.float64) - alpha * acc).astype(theta.dtype)
+    return theta
+
+
+def _bf16_round(x64: np.ndarray) -> np.ndarray:
+    """double -> bfloat16 bits, round to nearest even, vectorised (finite inputs).
+    The candidate below x is found from the float32 truncation, then the nearer of the two
+    neighbouring bfloat16 values is taken in double, ties to the even one."""
+    f = x64.astype(np.float32)                       # may already round up; fix below in double
+    bits = f.view(np.uint32)
+    lo = (bits & np.uint32(0xFFFF0000))
+    lo_v = lo.view(np.float32).astype(np.float64)
+    # make lo the bfloat16 value at or below |x| (towards zero)
+    toward = np.abs(lo_v) > np.abs(x64)
+    lo = np.where(toward, lo - np.uint32(0x10000), lo).astype(np.uint32)
+    lo_v = lo.view(np.float32).astype(np.float64)
+    hi = (lo + np.uint32(0x10000)).astype(np.uint32)
+    hi_v = hi.view(np.float32).astype(np.float64)
+    d_lo, d_hi = np.abs(x64 - lo_v), np.abs(hi_v - x64)
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (((lo >> np.uint32(16)) & np.uint32(1)) == 1))
+    return (np.where(take_hi, hi, lo) >> np.uint32(16)).astype(np.uint16)
+
+
+def lookup(W, dtype, D, ids):
+    """predict of Algorithm 1 for an embedding model: the vectors of the given words (rows of
+    the table, widened to float32; padding columns dropped)."""
+    ids = np.asarray(ids, dtype=np.int64)
+    rows = W[ids, :D]
+    return bf16_to_f32(rows) if dtype == BF16 else rows.astype(np.float32)
+
+
+def cosine_difference(A, B, dtype, D):
+    """Section 4.4: difference between the embeddings of every word before (A) and after (B)
+    further training, 1 - cos(A[r], B[r]) per row, in double.  Where the paper is silent: a
+    row that is zero in both tables has difference 0, one that is zero in only one has 1."""
+    a = (bf16_to_f32(A[:, :D]) if dtype == BF16 else A[:, :D]).astype(np.float64)
+    b = (bf16_to_f32(B[:, :D]) if dtype == BF16 else B[:, :D]).astype(np.float64)
+    dot = (a * b).sum(axis=1)
+    na, nb = (a * a).sum(axis=1), (b * b).sum(axis=1)
+    out = np.ones(a.shape[0], dtype=np.float64)
+    ok = (na > 0) & (nb > 0)
+    out[ok] = 1.0 - dot[ok] / np.sqrt(na[ok] * nb[ok])
+    out[(na == 0) & (nb == 0)] = 0.0
+    return out
+
+
 # ---------------------------------------------------------------- staleness
 def staleness(G_i, G_j) -> int:
     """Section 3.1: |G_i u G_j| - |G_i n G_j| for the set G_i of gradients model i had

@@ -371,3 +371,60 @@ def test_applying_a_summed_gradient_is_applying_its_parts():
     oracle.dasgd_apply_table(W1, D, oracle.F32, [oracle.grad_add_rows(ad, bd, D)], 0.5)
     oracle.dasgd_apply_table(W2, D, oracle.F32, [ad, bd], 0.5)
     assert np.array_equal(W1, W2)
+
+
+# ------------------------------------------------------------------ dense apply, lookup, cosine difference
+def test_vectorised_bf16_rounding_is_the_scalar_one():
+    rng = np.random.default_rng(8)
+    x = np.concatenate([rng.standard_normal(30_000) * rng.choice([1e-30, 1e-3, 1.0, 1e5, 1e30], 30_000),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 0.99609375 + 2.0 ** -10, 3.0e38]])
+    got = oracle._bf16_round(x)
+    want = np.array([oracle.double_to_bf16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+def test_dense_apply_is_eq1_and_the_sparse_apply_with_every_row_listed():
+    rng = np.random.default_rng(9)
+    V, D = 50, 6
+    theta0 = rng.standard_normal(V * D).astype(np.float32)
+    g = [rng.standard_normal(V * D).astype(np.float32) for _ in range(4)]
+    # K = 0: Eq. 1 in double, rounded once
+    t = oracle.dense_apply(theta0.copy(), oracle.F32, g[:1], 0.1)
+    want = (theta0.astype(np.float64) - float(np.float32(0.1)) * g[0].astype(np.float64)).astype(np.float32)
+    assert np.array_equal(t, want)
+    # a dense gradient is a sparse one that lists every row: same result as the sparse routine, bit for bit
+    t = oracle.dense_apply(theta0.copy(), oracle.F32, g, 0.025)
+    W = theta0.copy().reshape(V, D)
+    ids = np.arange(V, dtype=np.int32)
+    oracle.dasgd_apply_table(W, D, oracle.F32, [(ids, x.reshape(V, D)) for x in g], 0.025)
+    assert np.array_equal(t, W.reshape(-1))
+    # bf16: one rounding from the exact sum
+    tb = oracle._bf16_round(theta0.astype(np.float64))
+    t2 = oracle.dense_apply(tb.copy(), oracle.BF16, g, 0.025)
+    Wb = tb.copy().reshape(V, D)
+    oracle.dasgd_apply_table(Wb, D, oracle.BF16, [(ids, x.reshape(V, D)) for x in g], 0.025)
+    assert np.array_equal(t2, Wb.reshape(-1))
+    # no gradients: nothing moves
+    assert np.array_equal(oracle.dense_apply(theta0.copy(), oracle.F32, [], 0.5), theta0)
+
+
+def test_lookup_and_cosine_difference_closed_forms():
+    W = np.array([[3, 4, 9], [4, 3, 9], [0, 0, 9], [-3, -4, 9], [6, 8, 9], [4, -3, 9]], dtype=np.float32)   # last column = padding
+    rows = oracle.lookup(W, oracle.F32, 2, [4, 0, 0])
+    assert rows.dtype == np.float32 and rows.tolist() == [[6, 8], [3, 4], [3, 4]]
+    A = W[[0, 0, 0, 0, 0, 2, 2]]
+    Bt = W[[0, 1, 3, 4, 5, 2, 0]]
+    d = oracle.cosine_difference(A, Bt, oracle.F32, 2)
+    # same vector 0; (3,4).(4,3) = 24/25; opposite 2; scaled copy 0; orthogonal 1; zero vs zero 0; zero vs non-zero 1
+    assert np.allclose(d, [0.0, 0.04, 2.0, 0.0, 1.0, 0.0, 1.0], atol=1e-15)
+    rng = np.random.default_rng(10)
+    X, Y = rng.standard_normal((40, 7)).astype(np.float32), rng.standard_normal((40, 7)).astype(np.float32)
+    d = oracle.cosine_difference(X, Y, oracle.F32, 7)
+    assert np.allclose(d, oracle.cosine_difference(Y, X, oracle.F32, 7), atol=1e-15)            # symmetric
+    assert np.allclose(d, oracle.cosine_difference(3 * X, 0.5 * Y, oracle.F32, 7), atol=1e-12)  # scale-free
+    assert ((d >= 0) & (d <= 2)).all()
+    t = torch.nn.functional.cosine_similarity(torch.from_numpy(X).double(), torch.from_numpy(Y).double(), dim=1)
+    assert np.allclose(d, 1.0 - t.numpy(), atol=1e-12)
+    # bf16 tables are widened exactly
+    Xb = oracle._bf16_round(X.astype(np.float64))
+    assert np.array_equal(oracle.lookup(Xb, oracle.BF16, 7, [5]), oracle.bf16_to_f32(Xb[[5]]))
