@@ -9,6 +9,9 @@
  *   train(minibatch) incl. peer messages -> tensair_step
  *   a mini-batch waiting in the operator's input queue -> tensair_prefetch (optional)
  *   gradients += gradient (the buffer sent every maxGradBuffer steps) -> tensair_grad_add
+ *   apply_gradient for a dense model                 -> tensair_dense_apply
+ *   predict(msg) for an embedding model              -> tensair_lookup
+ *   cosine difference of two embedding tables (Section 4.4) -> tensair_cosine_difference
  *
  * Conventions for every call
  *   - Plain C ABI.  Pointers marked DEVICE point to GPU memory owned by the caller;
@@ -158,6 +161,28 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own,
  * Uses the same index scratch as tensair_dasgd_apply: calls on one model must be on one stream. */
 int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensair_sparse_grad *b,
                      tensair_sparse_grad *out, void *stream);
+
+/* apply_gradient of Algorithm 1 / Eq. 1 for a dense model (Section 4, "Sparse vs. Dense Models":
+ * every variable receives gradient), for the own gradient and the gradients received from peers
+ * at once: theta[i] <- theta[i] - lr * (grads[0][i] + ... + grads[n_grads-1][i]), the sum taken
+ * in fp32 in that order, one rounding on store (round-to-nearest-even for bf16).
+ * theta: DEVICE [n] of dtype, 16-byte aligned.  grads: HOST array of n_grads DEVICE pointers to
+ * fp32 [n] blocks, each 16-byte aligned, n_grads <= TENSAIR_MAX_PEERS + 1.  Needs no model handle. */
+int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,
+                        float lr, void *stream);
+
+/* predict of Algorithm 1 for an embedding model: the vectors of n words.  table: 0 = W_in (the
+ * word vectors), 1 = W_out.  ids: DEVICE int32[n]; out: DEVICE fp32 [n][dim], 16-byte aligned
+ * (bf16 tables are widened, padding columns dropped).  An id outside [0, vocab) yields a row of
+ * zeros and TENSAIR_EDATA from tensair_status. */
+int tensair_lookup(tensair_model *m, int32_t table, const int32_t *ids, int64_t n, float *out, void *stream);
+
+/* Section 4.4: how far training has moved every word, diff[r] = 1 - cos(a[r], b[r]) for two tables
+ * of the same shape and type (DEVICE, [vocab][row_stride], 16-byte aligned); diff: DEVICE fp32
+ * [vocab].  A row that is zero in both tables has difference 0, one that is zero in only one has 1.
+ * Needs no model handle. */
+int tensair_cosine_difference(const void *a, const void *b, int32_t dtype, int64_t vocab, int32_t dim,
+                              int32_t row_stride, float *diff, void *stream);
 
 /* train() of Algorithm 1 for one mini-batch plus the peer gradients that arrived:
  * tensair_sgns_grad into own_out on the current tables, then tensair_dasgd_apply of

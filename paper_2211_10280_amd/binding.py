@@ -25,7 +25,8 @@ SYMBOLS = [
     "tensair_model_rebind", "tensair_model_alias", "tensair_pair_count", "tensair_sgns_grad",
     "tensair_dasgd_apply", "tensair_step", "tensair_status", "tensair_model_destroy",
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
-    "tensair_prefetch", "tensair_grad_add",
+    "tensair_prefetch", "tensair_grad_add", "tensair_dense_apply", "tensair_lookup",
+    "tensair_cosine_difference",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -94,6 +95,12 @@ def lib():
         L.tensair_prefetch.restype = C.c_int
         L.tensair_grad_add.argtypes = [vp, C.POINTER(SparseGrad), C.POINTER(SparseGrad), C.POINTER(SparseGrad), vp]
         L.tensair_grad_add.restype = C.c_int
+        L.tensair_dense_apply.argtypes = [vp, i32, i64, C.POINTER(vp), i32, C.c_float, vp]
+        L.tensair_dense_apply.restype = C.c_int
+        L.tensair_lookup.argtypes = [vp, i32, vp, i64, vp, vp]
+        L.tensair_lookup.restype = C.c_int
+        L.tensair_cosine_difference.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
+        L.tensair_cosine_difference.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
@@ -246,6 +253,25 @@ def tensair_grad_add(h, a: GradBuffers, b: GradBuffers, out: GradBuffers, stream
     _check(lib().tensair_grad_add(h, C.byref(a.c), C.byref(b.c), C.byref(out.c), _stream(stream)))
 
 
+def tensair_dense_apply(theta, grads, lr: float, stream=None):
+    """theta: 1-D float32 or bfloat16 tensor; grads: list of float32 tensors of the same length."""
+    dt = F32 if theta.dtype == torch.float32 else BF16
+    arr = (C.c_void_p * max(len(grads), 1))(*[g.data_ptr() for g in grads])
+    _check(lib().tensair_dense_apply(_ptr(theta), dt, theta.numel(), arr, len(grads), C.c_float(lr),
+                                     _stream(stream)))
+
+
+def tensair_lookup(h, table: int, ids, out, stream=None):
+    _check(lib().tensair_lookup(h, table, _ptr(ids), ids.numel(), _ptr(out), _stream(stream)))
+
+
+def tensair_cosine_difference(a, b, dim: int, diff, stream=None):
+    """a, b: [vocab, row_stride] tables of the same dtype; diff: float32 [vocab]."""
+    dt = F32 if a.dtype == torch.float32 else BF16
+    _check(lib().tensair_cosine_difference(_ptr(a), _ptr(b), dt, a.shape[0], dim, a.shape[1], _ptr(diff),
+                                           _stream(stream)))
+
+
 def tensair_status(h, stream=None):
     _check(lib().tensair_status(h, _stream(stream)))
 
@@ -316,6 +342,9 @@ class Model:
 
     def step(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
         tensair_step(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+
+    def lookup(self, table, ids, out):
+        tensair_lookup(self.h, table, ids, out)
 
     def grad_add(self, a, b, out):
         tensair_grad_add(self.h, a, b, out)

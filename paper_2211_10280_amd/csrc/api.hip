@@ -903,6 +903,78 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
     return TENSAIR_OK;
 }
 
+int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,
+                        float lr, void *stream)
+{
+    if (!theta || (n_grads > 0 && !grads)) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    if (dtype != TENSAIR_F32 && dtype != TENSAIR_BF16) return fail(TENSAIR_EINVAL, "unknown dtype");
+    if (n < 0) return fail(TENSAIR_EINVAL, "n is negative");
+    if (n_grads < 0 || n_grads > TENSAIR_MAX_PEERS + 1)
+        return fail(TENSAIR_ECAPACITY, "n_grads %d outside 0..%d", n_grads, TENSAIR_MAX_PEERS + 1);
+    if (!(lr == lr)) return fail(TENSAIR_EINVAL, "lr is NaN");
+    if ((uintptr_t)theta & 15) return fail(TENSAIR_EINVAL, "theta must be 16-byte aligned");
+    DenseApplyArgs a;
+    memset(&a, 0, sizeof(a));
+    a.theta = theta;
+    a.n = n;
+    a.n_grads = n_grads;
+    a.dtype = dtype;
+    a.lr = lr;
+    for (int k = 0; k < n_grads; ++k) {
+        if (!grads[k]) return fail(TENSAIR_EINVAL, "grads[%d] is NULL", k);
+        if ((uintptr_t)grads[k] & 15) return fail(TENSAIR_EINVAL, "grads[%d] must be 16-byte aligned", k);
+        a.grads[k] = grads[k];
+    }
+    if (n == 0 || n_grads == 0) return TENSAIR_OK;
+    tn_launch_dense_apply(a, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_lookup(tensair_model *m, int32_t table, const int32_t *ids, int64_t n, float *out, void *stream)
+{
+    if (!m || (n > 0 && (!ids || !out))) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    if (table != 0 && table != 1) return fail(TENSAIR_EINVAL, "table must be 0 (W_in) or 1 (W_out)");
+    if (n < 0) return fail(TENSAIR_EINVAL, "n is negative");
+    if ((uintptr_t)out & 15) return fail(TENSAIR_EINVAL, "out must be 16-byte aligned");
+    const tensair_config &c = m->cfg;
+    LookupArgs a;
+    a.table = table ? m->w_out : m->w_in;
+    a.ids = ids;
+    a.out = out;
+    a.n = n;
+    a.V = c.vocab;
+    a.D = c.dim;
+    a.stride = c.row_stride;
+    a.dtype = c.dtype;
+    a.status = m->status;
+    tn_launch_lookup(a, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_cosine_difference(const void *a, const void *b, int32_t dtype, int64_t vocab, int32_t dim,
+                              int32_t row_stride, float *diff, void *stream)
+{
+    if (!a || !b || !diff) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    if (dtype != TENSAIR_F32 && dtype != TENSAIR_BF16) return fail(TENSAIR_EINVAL, "unknown dtype");
+    if (vocab < 0 || vocab > 0x7FFFFFFFLL) return fail(TENSAIR_EINVAL, "vocab out of range");
+    if (dim < 4 || dim > TENSAIR_MAX_DIM || dim % 4) return fail(TENSAIR_EINVAL, "dim must be a multiple of 4 in 4..1024");
+    if (row_stride < dim || row_stride % 4) return fail(TENSAIR_EINVAL, "row_stride must be >= dim and a multiple of 4");
+    if (((uintptr_t)a | (uintptr_t)b) & 15) return fail(TENSAIR_EINVAL, "tables must be 16-byte aligned");
+    CosineArgs c;
+    c.a = a;
+    c.b = b;
+    c.diff = diff;
+    c.V = vocab;
+    c.D = dim;
+    c.stride = row_stride;
+    c.dtype = dtype;
+    tn_launch_cosine_diff(c, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
 int tensair_status(tensair_model *m, void *stream)
 {
     if (!m) return fail(TENSAIR_EINVAL, "model is NULL");

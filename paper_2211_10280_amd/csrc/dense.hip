@@ -1,0 +1,154 @@
+// Three streaming operations around the worker step (TensAIR, arXiv 2211.10280):
+//   k_dense_apply   apply_gradient of Algorithm 1 / Eq. 1 for a dense model (Section 4, "Sparse vs.
+//                   Dense Models": every variable receives gradient): theta <- theta - alpha * sum_k g_k
+//                   for the own gradient and the gradients received from peers, one pass, one rounding
+//   k_lookup        predict of Algorithm 1 for an embedding model: the vectors of the given words
+//   k_cosine_diff   Section 4.4: 1 - cos between the embeddings of every word in two tables
+// All three are bound by HBM bandwidth: every byte is touched once, loads are 16 bytes per lane.
+#include "dev_common.h"
+#include "kernels.h"
+
+// ---------------------------------------------------------------- dense apply
+// a thread takes chunks of 4 elements, grid-strided; the gradients of a chunk are loaded four
+// sources at a time and summed in source order
+template <typename T>
+__global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
+{
+    const i64 n4 = a.n >> 2;
+    const float neg_lr = -a.lr;
+    T *theta = (T *)a.theta;
+    const i64 stride = (i64)gridDim.x * BLOCK;
+    for (i64 c = (i64)blockIdx.x * BLOCK + threadIdx.x; c < n4; c += stride) {
+        float4 w = ld4(theta + 4 * c);
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k0 = 0; k0 < a.n_grads; k0 += 4) {
+            float4 x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                x[j] = (k0 + j < a.n_grads) ? ld4(a.grads[k0 + j] + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc.x += x[j].x;
+                acc.y += x[j].y;
+                acc.z += x[j].z;
+                acc.w += x[j].w;
+            }
+        }
+        w.x = fmaf(neg_lr, acc.x, w.x);
+        w.y = fmaf(neg_lr, acc.y, w.y);
+        w.z = fmaf(neg_lr, acc.z, w.z);
+        w.w = fmaf(neg_lr, acc.w, w.w);
+        st4(theta + 4 * c, w);
+    }
+    // the last n mod 4 elements, one thread each
+    const i64 tail0 = n4 << 2;
+    const i64 t = tail0 + (i64)blockIdx.x * BLOCK + threadIdx.x;
+    if (blockIdx.x == 0 && t < a.n) {
+        float acc = 0.f;
+        for (int k = 0; k < a.n_grads; ++k) acc += a.grads[k][t];
+        if (sizeof(T) == 4) {
+            float *p = (float *)a.theta + t;
+            *p = fmaf(neg_lr, acc, *p);
+        } else {
+            bf16_t *p = (bf16_t *)a.theta + t;
+            *p = f32_to_bf16(fmaf(neg_lr, acc, bf16_to_f32(*p)));
+        }
+    }
+}
+
+void tn_launch_dense_apply(const DenseApplyArgs &a, hipStream_t st)
+{
+    const i64 n4 = a.n >> 2;
+    i64 want = (n4 + BLOCK - 1) / BLOCK;
+    if (want < 1) want = 1;
+    const int blocks = (int)(want > 16384 ? 16384 : want);
+    if (a.dtype == 0) hipLaunchKernelGGL(k_dense_apply<float>, dim3(blocks), dim3(BLOCK), 0, st, a);
+    else hipLaunchKernelGGL(k_dense_apply<bf16_t>, dim3(blocks), dim3(BLOCK), 0, st, a);
+}
+
+// ---------------------------------------------------------------- lookup
+// one wave per requested word: its row, widened to fp32, padding dropped; an id out of range yields
+// a row of zeros and sets the status word
+template <typename T, int ITERS>
+__global__ void __launch_bounds__(BLOCK) k_lookup(LookupArgs a)
+{
+    const int lane = lane_id();
+    const int C4 = a.D >> 2;
+    const i64 nw = (i64)gridDim.x * WAVES_PER_BLOCK;
+    for (i64 i = (i64)blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6)); i < a.n; i += nw) {
+        const int id = a.ids[i];
+        float4 r[ITERS];
+        if ((u32)id < (u32)a.V) {
+            load_row<T, ITERS>(r, (const T *)a.table + (size_t)id * a.stride, C4, lane);
+        } else {
+            zero_row<ITERS>(r);
+            if (lane == 0) atomicOr(a.status, ST_BAD_ID);
+        }
+        store_row<float, ITERS>(a.out + (size_t)i * a.D, r, C4, lane);
+    }
+}
+
+template <typename T>
+static void launch_lookup_t(const LookupArgs &a, hipStream_t st)
+{
+    const int iters = (a.D / 4 + WAVE - 1) / WAVE;
+    i64 want = (a.n + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int blocks = (int)(want > 65536 ? 65536 : want);
+    switch (iters) {
+    case 1: hipLaunchKernelGGL((k_lookup<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_lookup<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((k_lookup<T, 3>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_lookup<T, 4>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    }
+}
+
+void tn_launch_lookup(const LookupArgs &a, hipStream_t st)
+{
+    if (a.n <= 0) return;
+    if (a.dtype == 0) launch_lookup_t<float>(a, st);
+    else launch_lookup_t<bf16_t>(a, st);
+}
+
+// ---------------------------------------------------------------- cosine difference
+// one wave per row: the three sums <a,b>, <a,a>, <b,b> reduced across the wave, then
+// 1 - <a,b> / sqrt(<a,a> <b,b>); a row that is zero in both tables gives 0, in one of them 1
+template <typename T, int ITERS>
+__global__ void __launch_bounds__(BLOCK) k_cosine_diff(CosineArgs a)
+{
+    const int lane = lane_id();
+    const int C4 = a.D >> 2;
+    const i64 nw = (i64)gridDim.x * WAVES_PER_BLOCK;
+    for (i64 r = (i64)blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6)); r < a.V; r += nw) {
+        float4 x[ITERS], y[ITERS];
+        load_row<T, ITERS>(x, (const T *)a.a + (size_t)r * a.stride, C4, lane);
+        load_row<T, ITERS>(y, (const T *)a.b + (size_t)r * a.stride, C4, lane);
+        const float dot = wave_sum_dpp(dot_partial<ITERS>(x, y));
+        const float na = wave_sum_dpp(dot_partial<ITERS>(x, x));
+        const float nb = wave_sum_dpp(dot_partial<ITERS>(y, y));
+        float d;
+        if (na > 0.f && nb > 0.f) d = 1.0f - dot / (sqrtf(na) * sqrtf(nb));
+        else d = (na == 0.f && nb == 0.f) ? 0.f : 1.f;
+        if (lane == 0) a.diff[r] = d;
+    }
+}
+
+template <typename T>
+static void launch_cosine_t(const CosineArgs &a, hipStream_t st)
+{
+    const int iters = (a.D / 4 + WAVE - 1) / WAVE;
+    i64 want = (a.V + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int blocks = (int)(want > 65536 ? 65536 : want);
+    switch (iters) {
+    case 1: hipLaunchKernelGGL((k_cosine_diff<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_cosine_diff<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((k_cosine_diff<T, 3>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_cosine_diff<T, 4>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
+    }
+}
+
+void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st)
+{
+    if (a.V <= 0) return;
+    if (a.dtype == 0) launch_cosine_t<float>(a, st);
+    else launch_cosine_t<bf16_t>(a, st);
+}

@@ -159,5 +159,31 @@ struct GradSumArgs {
 void tn_launch_grad_sum_index(const GradSumArgs &g, hipStream_t st);   // index + scan
 void tn_launch_grad_sum_rows(const GradSumArgs &g, hipStream_t st);    // the rows themselves
 
+// ---- dense-model apply, embedding lookup, cosine difference between two tables
+struct DenseApplyArgs {
+    void *theta;                       // [n] f32 or bf16
+    const float *grads[TN_MAX_SRC];    // n_grads blocks of [n] fp32
+    i64 n;
+    int n_grads, dtype;
+    float lr;
+};
+void tn_launch_dense_apply(const DenseApplyArgs &a, hipStream_t st);
+struct LookupArgs {
+    const void *table;
+    const int *ids;
+    float *out;       // [n][D]
+    i64 n, V;
+    int D, stride, dtype;
+    int *status;
+};
+void tn_launch_lookup(const LookupArgs &a, hipStream_t st);
+struct CosineArgs {
+    const void *a, *b;
+    float *diff;      // [V]
+    i64 V;
+    int D, stride, dtype;
+};
+void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st);
+
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)
 void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);

@@ -436,6 +436,88 @@ def test_grad_add_of_real_gradients_and_errors():
     m.close()
 
 
+# ------------------------------------------------------------------ dense apply, lookup, cosine difference
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n,K", [(1, 1), (7, 3), (4096, 0), (1_000_003, 8), (300 * 4099, 32)])
+def test_dense_apply_parity(dtype, n, K):
+    """Eq. 1 on a dense model with K gradient blocks: fp32 within 1e-6 of the oracle's double sum (far inside
+    the 1e-4 bar), bf16 within 2 ulp; K = 0 leaves theta alone."""
+    _say("dense_apply", dtype, n, K)
+    rng = np.random.default_rng(n + K)
+    bd, od, tdt, _ = DT[dtype]
+    th = rng.standard_normal(n).astype(np.float32)
+    theta = th if dtype == "f32" else oracle._bf16_round(th.astype(np.float64))
+    grads = [(rng.standard_normal(n) * 0.5).astype(np.float32) for _ in range(K)]
+    d_theta = _tables_to_dev(theta.reshape(1, -1), dtype).reshape(-1)
+    d_grads = [torch.from_numpy(g).cuda() for g in grads]
+    B.tensair_dense_apply(d_theta, d_grads, 0.025)
+    torch.cuda.synchronize()
+    got = _tables_to_host(d_theta.reshape(1, -1), dtype).reshape(-1)
+    want = oracle.dense_apply(theta.copy(), od, grads, 0.025)
+    if K == 0:
+        assert np.array_equal(got, theta)
+    elif dtype == "f32":
+        assert np.abs(got.astype(np.float64) - want).max() <= 1e-6 * max(1.0, np.abs(want).max())
+        assert rel_l2(got, want) <= TOL_TABLE * 1e-2
+    else:
+        assert bf16_ulp_err(got, want, None) <= BF16_ULP
+    for g, dg in zip(grads, d_grads):
+        assert np.array_equal(dg.cpu().numpy(), g)
+
+
+def test_dense_apply_errors():
+    th = torch.zeros(64, device="cuda")
+    g = torch.zeros(64, device="cuda")
+    with pytest.raises(B.TensairError) as e:
+        B.tensair_dense_apply(th, [g] * 33, 0.1)            # more blocks than the boundary takes
+    assert e.value.code == B.ECAPACITY
+    with pytest.raises(B.TensairError) as e:
+        B.tensair_dense_apply(th[1:], [g[1:]], 0.1)         # not 16-byte aligned
+    assert e.value.code == B.EINVAL
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,D,stride", [(1000, 32, 32), (4099, 300, 304), (70, 1024, 1024)])
+def test_lookup_and_cosine_difference_parity(dtype, V, D, stride):
+    _say("lookup/cosine", dtype, V, D, stride)
+    bd, od, tdt, _ = DT[dtype]
+    A, Bt = _random_tables(V, D, stride, dtype, seed=V), _random_tables(V, D, stride, dtype, seed=V + 1)[0]
+    A_in, A_out = A
+    # a few special rows: equal, opposite, zero in both, zero in one
+    Bt[0] = A_in[0]
+    Bt[1, :D] = (A_in[1, :D] ^ np.uint16(0x8000)) if dtype == "bf16" else -A_in[1, :D]
+    A_in[2], Bt[2] = 0, 0
+    Bt[3] = 0
+    m = B.Model(V, D, bd, 2, 3, 16, 0, 1, np.ones(V, np.uint64), row_stride=stride,
+                tables=(_tables_to_dev(A_in, dtype), _tables_to_dev(A_out, dtype)))
+    rng = np.random.default_rng(V)
+    ids = rng.integers(0, V, size=777).astype(np.int32)
+    d_ids = torch.from_numpy(ids).cuda()
+    for table, W_np in ((0, A_in), (1, A_out)):
+        out = torch.full((ids.size, D), float("nan"), device="cuda")
+        m.lookup(table, d_ids, out)
+        m.status()
+        assert np.array_equal(out.cpu().numpy(), oracle.lookup(W_np, od, D, ids))        # a copy: bit-exact
+    # an id out of range: zeros and an error, no fault
+    bad = torch.tensor([5, V, -1], dtype=torch.int32, device="cuda")
+    out = torch.full((3, D), float("nan"), device="cuda")
+    m.lookup(0, bad, out)
+    with pytest.raises(B.TensairError) as e:
+        m.status()
+    assert e.value.code == B.EDATA and not out[1:].any().item()
+    assert np.array_equal(out[0].cpu().numpy(), oracle.lookup(A_in, od, D, [5])[0])
+    # cosine difference of the two tables
+    diff = torch.full((V,), float("nan"), device="cuda")
+    B.tensair_cosine_difference(m.w_in, _tables_to_dev(Bt, dtype), D, diff)
+    torch.cuda.synchronize()
+    want = oracle.cosine_difference(A_in, Bt, od, D)
+    got = diff.cpu().numpy().astype(np.float64)
+    _say(f"   cosine difference: max abs error {np.abs(got - want).max():.2e}, mean difference {want.mean():.4f}")
+    assert np.abs(got - want).max() <= 2e-6
+    assert got[0] <= 2e-6 and abs(got[1] - 2.0) <= 2e-6 and got[2] == 0.0 and got[3] == 1.0
+    m.close()
+
+
 # ------------------------------------------------------------------ prefetch of the coming mini-batch
 def _grad_snapshot(g, loss=None, seg_in=None, seg_out=None):
     ui, uo = g.sizes()
