@@ -50,8 +50,8 @@ def main():
                     help="every step self-contained (default: the next mini-batch is handed to tensair_prefetch "
                          "after each step, as it would be waiting in the worker's input queue)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
-    ap.add_argument("--op", choices=["step", "grad_add"], default="step",
-                    help="step: the worker step (the metric); grad_add: the gradient-buffer sum on its own")
+    ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine"], default="step",
+                    help="step: the worker step (the metric); the others time one of the further operations on its own")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU worker step; there is no multi-GPU path (--gpus must be 1)")
@@ -77,6 +77,8 @@ def main():
 
     if args.op == "grad_add":
         return bench_grad_add(args, cfg, tok, counts)
+    if args.op != "step":
+        return bench_streaming(args, cfg)
 
     worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch)
     model = worker.model
@@ -315,6 +317,117 @@ def bench_grad_add(args, cfg, tok, counts):
         cpu_t = (time.perf_counter() - t0) / reps
         out_json["cpu_baseline"] = {"value": (uo_in + uo_out) / cpu_t, "unit": "rows/s", "cores": 1, "kind": "oracle",
                                     "sample": f"{reps} sums of the same two gradients ({cpu_t:.3f} s each)"}
+    print(json.dumps(out_json), flush=True)
+
+
+def bench_streaming(args, cfg):
+    """dense_apply: theta of V*D elements, K+1 gradient blocks; lookup: 1 M random words; cosine: two tables."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2211_10280_amd import binding as B
+
+    V, D, e = cfg.vocab, cfg.dim, cfg.elem_bytes
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    odt = oracle.F32 if cfg.dtype == "f32" else oracle.BF16
+    S = args.steps if args.steps else 20
+    Wm = args.warmup if args.warmup is not None else 3
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def to_np(t):
+        return t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+    if args.op == "dense_apply":
+        n, K1 = V * D, cfg.peers + 1
+        theta = (torch.randn(n, device="cuda", generator=gen) * 0.1).to(tdt)
+        grads = [torch.randn(n, device="cuda", generator=gen) * 0.01 for _ in range(K1)]
+        call = lambda: B.tensair_dense_apply(theta, grads, cfg.lr)
+        alg = K1 * n * 4 + 2 * n * e
+        units, unit, kernel = n, "parameters/s", "k_dense_apply"
+        what = {"parameters": n, "gradient_blocks": K1}
+
+        def cpu():
+            m = min(n, 4_000_000)
+            th = to_np(theta[:m]).copy()
+            gs = [g[:m].cpu().numpy() for g in grads]
+            t0 = time.perf_counter()
+            oracle.dense_apply(th, odt, gs, cfg.lr)
+            return m / (time.perf_counter() - t0), f"the first {m} parameters, once"
+    elif args.op == "lookup":
+        n = 1_000_000
+        counts = np.ones(V, np.uint64)
+        m = B.Model(V, D, B.F32 if cfg.dtype == "f32" else B.BF16, cfg.window, cfg.negatives, 16, 0, cfg.seed, counts)
+        ids = torch.randint(0, V, (n,), device="cuda", generator=gen, dtype=torch.int32)
+        out = torch.empty((n, D), device="cuda")
+        call = lambda: m.lookup(0, ids, out)
+        alg = n * (D * e + D * 4 + 4)
+        units, unit, kernel = n, "words/s", "k_lookup"
+        what = {"words": n, "dim": D}
+
+        def cpu():
+            Wn, idn = to_np(m.w_in), ids.cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.lookup(Wn, odt, D, idn)
+            return n / (time.perf_counter() - t0), "the same lookup, once"
+    else:
+        a = (torch.randn((V, D), device="cuda", generator=gen) * 0.1).to(tdt)
+        b = (a.float() + torch.randn((V, D), device="cuda", generator=gen) * 0.02).to(tdt)
+        diff = torch.empty(V, device="cuda")
+        call = lambda: B.tensair_cosine_difference(a, b, D, diff)
+        alg = 2 * V * D * e + V * 4
+        units, unit, kernel = V, "words/s", "k_cosine_diff"
+        what = {"vocab": V, "dim": D}
+
+        def cpu():
+            m = min(V, 200_000)
+            an, bn = to_np(a[:m]), to_np(b[:m])
+            t0 = time.perf_counter()
+            oracle.cosine_difference(an, bn, odt, D)
+            return m / (time.perf_counter() - t0), f"the first {m} rows, once"
+
+    for _ in range(Wm):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(S):
+        call()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    k_s = ev0.elapsed_time(ev1) * 1e-3 / S      # one kernel per call, back to back on torch's current stream
+    # the plain copy kernel of known size, for the calibration of the HBM byte counters
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.tensair_copy_probe(dst, src, nbytes)
+    torch.cuda.synchronize()
+    del src, dst
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}_{args.op}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    out_json = {
+        "metric": {"dense_apply": "dense-model gradient application (Eq. 1 on every parameter)",
+                   "lookup": "embedding lookup (predict path)",
+                   "cosine": "cosine difference between two embedding tables"}[args.op],
+        "value": units / (elapsed / S), "unit": unit, "n_gpus": 1, "steps": S, "warmup": Wm,
+        "ms_per_step": elapsed / S * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 tables, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}:{args.op}", **what},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": alg / k_s / 1e9, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": alg / k_s / HBM_PEAK, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg, "avg_launch_ms": k_s * 1e3},
+    }
+    if not args.no_cpu_baseline:
+        v, sample = cpu()
+        out_json["cpu_baseline"] = {"value": v, "unit": unit, "cores": 1, "kind": "oracle", "sample": sample}
     print(json.dumps(out_json), flush=True)
 
 

@@ -908,7 +908,7 @@ int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *cons
 {
     if (!theta || (n_grads > 0 && !grads)) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     if (dtype != TENSAIR_F32 && dtype != TENSAIR_BF16) return fail(TENSAIR_EINVAL, "unknown dtype");
-    if (n < 0) return fail(TENSAIR_EINVAL, "n is negative");
+    if (n < 0 || n > ((int64_t)1 << 40)) return fail(TENSAIR_EINVAL, "n outside 0..2^40");
     if (n_grads < 0 || n_grads > TENSAIR_MAX_PEERS + 1)
         return fail(TENSAIR_ECAPACITY, "n_grads %d outside 0..%d", n_grads, TENSAIR_MAX_PEERS + 1);
     if (!(lr == lr)) return fail(TENSAIR_EINVAL, "lr is NaN");

@@ -9,25 +9,28 @@
 #include "kernels.h"
 
 // ---------------------------------------------------------------- dense apply
-// a thread takes chunks of 4 elements, grid-strided; the gradients of a chunk are loaded four
+// a thread takes one chunk of 4 elements; the gradients of the chunk are loaded DENSE_INFLIGHT
 // sources at a time and summed in source order
+#define DENSE_INFLIGHT 4
 template <typename T>
 __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
 {
     const i64 n4 = a.n >> 2;
     const float neg_lr = -a.lr;
     T *theta = (T *)a.theta;
-    const i64 stride = (i64)gridDim.x * BLOCK;
-    for (i64 c = (i64)blockIdx.x * BLOCK + threadIdx.x; c < n4; c += stride) {
+    // one chunk per thread, consecutive workgroups consecutive chunks: the K+2 streams then advance
+    // through memory together (a grid-stride loop over a fixed grid was 12 % slower)
+    const i64 c = (i64)blockIdx.x * BLOCK + threadIdx.x;
+    if (c < n4) {
         float4 w = ld4(theta + 4 * c);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int k0 = 0; k0 < a.n_grads; k0 += 4) {
-            float4 x[4];
+        for (int k0 = 0; k0 < a.n_grads; k0 += DENSE_INFLIGHT) {
+            float4 x[DENSE_INFLIGHT];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < DENSE_INFLIGHT; ++j)
                 x[j] = (k0 + j < a.n_grads) ? ld4(a.grads[k0 + j] + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < DENSE_INFLIGHT; ++j) {
                 acc.x += x[j].x;
                 acc.y += x[j].y;
                 acc.z += x[j].z;
@@ -61,7 +64,7 @@ void tn_launch_dense_apply(const DenseApplyArgs &a, hipStream_t st)
     const i64 n4 = a.n >> 2;
     i64 want = (n4 + BLOCK - 1) / BLOCK;
     if (want < 1) want = 1;
-    const int blocks = (int)(want > 16384 ? 16384 : want);
+    const int blocks = (int)want;
     if (a.dtype == 0) hipLaunchKernelGGL(k_dense_apply<float>, dim3(blocks), dim3(BLOCK), 0, st, a);
     else hipLaunchKernelGGL(k_dense_apply<bf16_t>, dim3(blocks), dim3(BLOCK), 0, st, a);
 }
@@ -93,7 +96,7 @@ static void launch_lookup_t(const LookupArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     i64 want = (a.n + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    const int blocks = (int)(want > 65536 ? 65536 : want);
+    const int blocks = (int)(want > 0x3FFFFFFF ? 0x3FFFFFFF : want);
     switch (iters) {
     case 1: hipLaunchKernelGGL((k_lookup<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
     case 2: hipLaunchKernelGGL((k_lookup<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
@@ -137,7 +140,7 @@ static void launch_cosine_t(const CosineArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     i64 want = (a.V + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    const int blocks = (int)(want > 65536 ? 65536 : want);
+    const int blocks = (int)(want > 0x3FFFFFFF ? 0x3FFFFFFF : want);
     switch (iters) {
     case 1: hipLaunchKernelGGL((k_cosine_diff<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
     case 2: hipLaunchKernelGGL((k_cosine_diff<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
