@@ -92,6 +92,9 @@ GRAD_CASES = [
     (3, 64, 64, 5_000, 0.5, 3, 4, 700, 100, "f32"),             # three rows take everything
     (100_000, 1024, 1024, 30_000, 1.0, 2, 3, 64, 5, "f32"),     # widest row (4 chunk passes), 17 key bits
     (300, 4, 4, 2_000, 1.0, 1, 0, 128, 0, "f32"),               # narrowest row, no negatives
+    (900, 520, 520, 6_000, 1.0, 2, 3, 96, 40, "bf16"),          # two full register sets + a tail of 8 elements
+    (900, 772, 776, 6_000, 1.0, 2, 3, 96, 40, "f32"),           # three + a tail of 4, padded stride
+    (900, 320, 320, 6_000, 1.0, 2, 3, 96, 40, "f32"),           # one + a full tail of 64
     (5_000_000, 8, 8, 50_000, 0.8, 4, 6, 2048, 3000, "f32"),    # 23 key bits: three radix passes
 ]
 
