@@ -415,7 +415,7 @@ __global__ void __launch_bounds__(BLOCK) k_grad_sum(GradSumArgs g, int nblocks)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) add_row<ITERS>(acc, x[j]);
             }
-            store_row<float, ITERS>(g.out_rows[tb] + (size_t)dst * a.D, acc, C4, lane);
+            store_row_s<float, ITERS>(g.out_rows[tb] + (size_t)dst * a.D, acc, C4, lane);
             if (lane == 0) g.out_ids[tb][dst] = (int)r;
         }
     }

@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(BLOCK) k_lookup(LookupArgs a)
             zero_row<ITERS>(r);
             if (lane == 0) atomicOr(a.status, ST_BAD_ID);
         }
-        store_row<float, ITERS>(a.out + (size_t)i * a.D, r, C4, lane);
+        store_row_s<float, ITERS>(a.out + (size_t)i * a.D, r, C4, lane);
     }
 }
 

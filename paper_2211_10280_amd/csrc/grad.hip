@@ -339,7 +339,11 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
             if (e < e_end) {
                 if (sg[x] != cur) {   // row `cur` is complete (or its share of it): write it out
                     float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
-                    store_row<float, ITERS>(dst, acc, C4, lane);
+                    // a finished gradient row is next read by the table update, long after this kernel:
+                    // written around the caches (with ordinary stores the update ran 4 % slower, paying
+                    // for the write-back of these lines), while partials are read again at once
+                    if (dest == 0) store_row_s<float, ITERS>(dst, acc, C4, lane);
+                    else store_row<float, ITERS>(dst, acc, C4, lane);
                     zero_row<ITERS>(acc);
                     cur = sg[x];
                     const int end = row_end(e);
@@ -350,7 +354,8 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
         }
     }
     float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
-    store_row<float, ITERS>(dst, acc, C4, lane);
+    if (dest == 0) store_row_s<float, ITERS>(dst, acc, C4, lane);
+    else store_row<float, ITERS>(dst, acc, C4, lane);
     // a long row begins in this tile: leave its tile for the kernel that chains the partials
     // (integer counter; the order of the list does not matter, every chain is independent)
     if (dest == 2 && lane == 0) a.long_list[atomicAdd(a.long_cnt, 1)] = tile;
