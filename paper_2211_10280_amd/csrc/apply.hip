@@ -106,12 +106,14 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 
 // Sum of the sources of one row (bits of S, ascending: own first, then peers), W <- W - lr * sum.
 // lane 32*tb + k holds the position `pos` of the row in source k and that source's row pointer.
-template <typename T, int ITERS>
+// STREAM: every access goes around the caches (non-temporal), for tables far larger than the caches.
+template <typename T, int ITERS, bool STREAM>
 __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos, int D, int C4, int lane,
                                            float neg_lr)
 {
     float4 w[ITERS], acc[ITERS];
-    load_row<T, ITERS>(w, wrow, C4, lane);
+    if (STREAM) load_row_s<T, ITERS>(w, wrow, C4, lane);
+    else load_row<T, ITERS>(w, wrow, C4, lane);
     zero_row<ITERS>(acc);
     while (S) {
         float4 x[4][ITERS];
@@ -121,7 +123,8 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
                 const int k = (int)__builtin_ctzll(S);
                 S &= S - 1ull;
                 const float *src = (const float *)rd_lane64(rows_ptr, k) + (size_t)(u32)rd_lane((int)pos, k) * D;
-                load_row<float, ITERS>(x[j], src, C4, lane);
+                if (STREAM) load_row_s<float, ITERS>(x[j], src, C4, lane);
+                else load_row<float, ITERS>(x[j], src, C4, lane);
             } else {
                 zero_row<ITERS>(x[j]);
             }
@@ -136,13 +139,14 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
         w[it].z = fmaf(neg_lr, acc[it].z, w[it].z);
         w[it].w = fmaf(neg_lr, acc[it].w, w[it].w);
     }
-    store_row<T, ITERS>(wrow, w, C4, lane);
+    if (STREAM) store_row_s<T, ITERS>(wrow, w, C4, lane);
+    else store_row<T, ITERS>(wrow, w, C4, lane);
 }
 
 #ifndef APPLY_MAX_WAVES
 #define APPLY_MAX_WAVES 6
 #endif
-template <typename T, int ITERS, int G>
+template <typename T, int ITERS, int G, bool STREAM>
 __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(1, APPLY_MAX_WAVES)))
 k_apply(ApplyArgs a, int nblocks)
 {
@@ -212,12 +216,12 @@ k_apply(ApplyArgs a, int nblocks)
             const u32 pos = st + (u32)__popcll(m & ((1ull << b) - 1ull));
             const bool ok = mine && ((m >> b) & 1ull) && (pos < (u32)U);
             const u64 S = __ballot(ok);   // bit 32*tb + k: source k has row r
-            update_row<T, ITERS>(table + (size_t)r * a.stride, S, rows_ptr, pos, a.D, C4, lane, neg_lr);
+            update_row<T, ITERS, STREAM>(table + (size_t)r * a.stride, S, rows_ptr, pos, a.D, C4, lane, neg_lr);
         }
     }
 }
 
-template <typename T>
+template <typename T, bool STREAM>
 static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
@@ -226,10 +230,10 @@ static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
     const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     dim3 grid(nblocks), blk(BLOCK);
     switch (iters) {
-    case 1: hipLaunchKernelGGL((k_apply<T, 1, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
-    case 2: hipLaunchKernelGGL((k_apply<T, 2, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
-    case 3: hipLaunchKernelGGL((k_apply<T, 3, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
-    default: hipLaunchKernelGGL((k_apply<T, 4, APPLY_G>), grid, blk, 0, st, a, nblocks); break;
+    case 1: hipLaunchKernelGGL((k_apply<T, 1, APPLY_G, STREAM>), grid, blk, 0, st, a, nblocks); break;
+    case 2: hipLaunchKernelGGL((k_apply<T, 2, APPLY_G, STREAM>), grid, blk, 0, st, a, nblocks); break;
+    case 3: hipLaunchKernelGGL((k_apply<T, 3, APPLY_G, STREAM>), grid, blk, 0, st, a, nblocks); break;
+    default: hipLaunchKernelGGL((k_apply<T, 4, APPLY_G, STREAM>), grid, blk, 0, st, a, nblocks); break;
     }
 }
 
@@ -257,8 +261,14 @@ void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream
 
 void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st)
 {
-    if (a.dtype == 0) launch_apply_t<float>(a, st);
-    else launch_apply_t<bf16_t>(a, st);
+    // Tables that dwarf the caches (256 MB memory-side, 32 MB of L2) are updated around them: a row
+    // touched here is not touched again before megabytes of others have passed, and what the gradient
+    // calculation left in the caches (the frequent rows, which its next pass reads again) survives the
+    // update.  Measured at a 2 x 1.2 GB model: step 0.953 -> 0.930 ms.  Small tables stay cached.
+    const i64 elem = a.dtype == 0 ? 4 : 2;
+    const bool stream = 2 * a.V * (i64)a.stride * elem > ((i64)1 << 30);
+    if (a.dtype == 0) stream ? launch_apply_t<float, true>(a, st) : launch_apply_t<float, false>(a, st);
+    else stream ? launch_apply_t<bf16_t, true>(a, st) : launch_apply_t<bf16_t, false>(a, st);
 }
 
 // ---------------------------------------------------------------- sum of sparse gradients
