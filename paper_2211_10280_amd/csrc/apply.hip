@@ -417,7 +417,7 @@ __global__ void __launch_bounds__(BLOCK) k_grad_sum(GradSumArgs g, int nblocks)
                         const int k = (int)__builtin_ctzll(S);
                         S &= S - 1ull;
                         const float *src = (const float *)rd_lane64(rows_ptr, k) + (size_t)(u32)rd_lane((int)pos, k) * a.D;
-                        load_row<float, ITERS>(x[j], src, C4, lane);
+                        load_row_s<float, ITERS>(x[j], src, C4, lane);   // read once: around the caches
                     } else {
                         zero_row<ITERS>(x[j]);
                     }

@@ -12,7 +12,8 @@
 // a thread takes one chunk of 4 elements; the gradients of the chunk are loaded DENSE_INFLIGHT
 // sources at a time and summed in source order
 #define DENSE_INFLIGHT 4
-template <typename T>
+// STREAM: all accesses around the caches, for models far larger than them (+9 % at 300 M parameters)
+template <typename T, bool STREAM>
 __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
 {
     const i64 n4 = a.n >> 2;
@@ -22,13 +23,14 @@ __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
     // through memory together (a grid-stride loop over a fixed grid was 12 % slower)
     const i64 c = (i64)blockIdx.x * BLOCK + threadIdx.x;
     if (c < n4) {
-        float4 w = ld4(theta + 4 * c);
+        float4 w = STREAM ? ld4s(theta + 4 * c) : ld4(theta + 4 * c);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int k0 = 0; k0 < a.n_grads; k0 += DENSE_INFLIGHT) {
             float4 x[DENSE_INFLIGHT];
 #pragma unroll
             for (int j = 0; j < DENSE_INFLIGHT; ++j)
-                x[j] = (k0 + j < a.n_grads) ? ld4(a.grads[k0 + j] + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                x[j] = (k0 + j >= a.n_grads) ? make_float4(0.f, 0.f, 0.f, 0.f)
+                       : (STREAM ? ld4s(a.grads[k0 + j] + 4 * c) : ld4(a.grads[k0 + j] + 4 * c));
 #pragma unroll
             for (int j = 0; j < DENSE_INFLIGHT; ++j) {
                 acc.x += x[j].x;
@@ -41,7 +43,8 @@ __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
         w.y = fmaf(neg_lr, acc.y, w.y);
         w.z = fmaf(neg_lr, acc.z, w.z);
         w.w = fmaf(neg_lr, acc.w, w.w);
-        st4(theta + 4 * c, w);
+        if (STREAM) st4s(theta + 4 * c, w);
+        else st4(theta + 4 * c, w);
     }
     // the last n mod 4 elements, one thread each
     const i64 tail0 = n4 << 2;
@@ -65,8 +68,14 @@ void tn_launch_dense_apply(const DenseApplyArgs &a, hipStream_t st)
     i64 want = (n4 + BLOCK - 1) / BLOCK;
     if (want < 1) want = 1;
     const int blocks = (int)want;
-    if (a.dtype == 0) hipLaunchKernelGGL(k_dense_apply<float>, dim3(blocks), dim3(BLOCK), 0, st, a);
-    else hipLaunchKernelGGL(k_dense_apply<bf16_t>, dim3(blocks), dim3(BLOCK), 0, st, a);
+    const bool stream = a.n * (a.dtype == 0 ? 4 : 2) + (i64)a.n_grads * a.n * 4 > ((i64)1 << 30);
+    if (a.dtype == 0) {
+        if (stream) hipLaunchKernelGGL((k_dense_apply<float, true>), dim3(blocks), dim3(BLOCK), 0, st, a);
+        else hipLaunchKernelGGL((k_dense_apply<float, false>), dim3(blocks), dim3(BLOCK), 0, st, a);
+    } else {
+        if (stream) hipLaunchKernelGGL((k_dense_apply<bf16_t, true>), dim3(blocks), dim3(BLOCK), 0, st, a);
+        else hipLaunchKernelGGL((k_dense_apply<bf16_t, false>), dim3(blocks), dim3(BLOCK), 0, st, a);
+    }
 }
 
 // ---------------------------------------------------------------- lookup
@@ -123,8 +132,8 @@ __global__ void __launch_bounds__(BLOCK) k_cosine_diff(CosineArgs a)
     const i64 nw = (i64)gridDim.x * WAVES_PER_BLOCK;
     for (i64 r = (i64)blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6)); r < a.V; r += nw) {
         float4 x[ITERS], y[ITERS];
-        load_row<T, ITERS>(x, (const T *)a.a + (size_t)r * a.stride, C4, lane);
-        load_row<T, ITERS>(y, (const T *)a.b + (size_t)r * a.stride, C4, lane);
+        load_row_s<T, ITERS>(x, (const T *)a.a + (size_t)r * a.stride, C4, lane);   // read once
+        load_row_s<T, ITERS>(y, (const T *)a.b + (size_t)r * a.stride, C4, lane);
         const float dot = wave_sum_dpp(dot_partial<ITERS>(x, y));
         const float na = wave_sum_dpp(dot_partial<ITERS>(x, x));
         const float nb = wave_sum_dpp(dot_partial<ITERS>(y, y));

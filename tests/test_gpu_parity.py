@@ -441,7 +441,8 @@ def test_grad_add_of_real_gradients_and_errors():
 
 # ------------------------------------------------------------------ dense apply, lookup, cosine difference
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("n,K", [(1, 1), (7, 3), (4096, 0), (1_000_003, 8), (300 * 4099, 32)])
+@pytest.mark.parametrize("n,K", [(1, 1), (7, 3), (4096, 0), (1_000_003, 8), (300 * 4099, 32),
+                                 (2 ** 25 + 3, 8)])      # above 1 GiB in all: the variant that goes around the caches
 def test_dense_apply_parity(dtype, n, K):
     """Eq. 1 on a dense model with K gradient blocks: fp32 within 1e-6 of the oracle's double sum (far inside
     the 1e-4 bar), bf16 within 2 ulp; K = 0 leaves theta alone."""
