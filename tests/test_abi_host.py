@@ -53,3 +53,37 @@ def test_host_side_argument_checks():
     h = C.c_void_p()
     assert L.tensair_model_init(C.byref(h), C.byref(good), None, None, 1, None, None, 0, None) == B.EINVAL
     assert h.value is None
+
+
+def test_host_side_argument_checks_of_the_further_entry_points():
+    """Everything below is refused on the host, before any GPU call is made."""
+    L = B.lib()
+    buf = (C.c_float * 64)()
+    addr = C.addressof(buf)
+    aligned = (addr + 15) & ~15
+    ptrs = (C.c_void_p * 40)(*([aligned] * 40))
+    # dense apply: NULL theta, unknown dtype, negative n, too many blocks, NaN step, misaligned pointers
+    assert L.tensair_dense_apply(None, B.F32, 16, ptrs, 1, 0.1, None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned, 7, 16, ptrs, 1, 0.1, None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned, B.F32, -1, ptrs, 1, 0.1, None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned, B.F32, 16, ptrs, B.MAX_PEERS + 2, 0.1, None) == B.ECAPACITY
+    assert L.tensair_dense_apply(aligned, B.F32, 16, ptrs, 1, float("nan"), None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned + 4, B.F32, 16, ptrs, 1, 0.1, None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned, B.F32, 16, None, 1, 0.1, None) == B.EINVAL
+    # nothing to do is not an error and launches nothing
+    assert L.tensair_dense_apply(aligned, B.F32, 0, ptrs, 1, 0.1, None) == B.OK
+    assert L.tensair_dense_apply(aligned, B.F32, 16, ptrs, 0, 0.1, None) == B.OK
+    # cosine difference: NULL, dtype, shape
+    assert L.tensair_cosine_difference(None, aligned, B.F32, 4, 4, 4, aligned, None) == B.EINVAL
+    assert L.tensair_cosine_difference(aligned, aligned, 3, 4, 4, 4, aligned, None) == B.EINVAL
+    assert L.tensair_cosine_difference(aligned, aligned, B.F32, 4, 6, 8, aligned, None) == B.EINVAL
+    assert L.tensair_cosine_difference(aligned, aligned, B.F32, 4, 8, 4, aligned, None) == B.EINVAL
+    assert L.tensair_cosine_difference(aligned, aligned, B.F32, -1, 4, 4, aligned, None) == B.EINVAL
+    # calls that need a model
+    assert L.tensair_lookup(None, 0, None, 0, None, None) == B.EINVAL
+    assert L.tensair_grad_add(None, None, None, None, None) == B.EINVAL
+    assert L.tensair_prefetch(None, None, 1, 0, 0, 0, None) == B.EINVAL
+    assert L.tensair_step(None, None, 1, 0, 0, 0, None, 0, 0.1, None, None, None) == B.EINVAL
+    assert L.tensair_sgns_grad(None, None, 1, 0, 0, 0, None, None, None, None, None, None) == B.EINVAL
+    assert L.tensair_profile(None, 1) == B.EINVAL
+    assert L.tensair_model_destroy(None) == B.OK             # destroying nothing is allowed
