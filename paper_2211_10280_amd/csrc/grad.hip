@@ -22,14 +22,13 @@
 #endif
 
 // ---------------------------------------------------------------- forward
-// A row of D elements held by one wave for the forward pass.  NQ float4 registers per lane (lane l
-// owns chunks l, l+64, ..., bounds-checked against D/4) and, if TAIL, one more float per lane for the
-// elements from 256*NQ on (at most 64 of them).  The second form is for dimensions just above a
-// multiple of 256 -- D = 300 is 256 + 44 -- where a float4 that only 11 lanes use would cost every
-// lane four registers per row; with one float instead, twice as many rows fit in flight at the same
-// occupancy.
+// A row of D elements held by one wave.  NQ float4 registers per lane (lane l owns chunks l, l+64, ...,
+// bounds-checked against D/4) and, if TAIL, one more float per lane for the elements from 256*NQ on (at
+// most 64 of them).  The second form is for dimensions just above a multiple of 256 -- D = 300 is
+// 256 + 44 -- where a float4 that only 11 lanes use would cost every lane four registers per row; with
+// one float instead, twice as many rows fit in flight at the same occupancy.
 template <int NQ, bool TAIL>
-struct FwdRow {
+struct WaveRow {
     float4 q[NQ];
     float t;
 
@@ -53,7 +52,7 @@ struct FwdRow {
         for (int it = 0; it < NQ; ++it) q[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         t = 0.f;
     }
-    __device__ __forceinline__ float dot(const FwdRow &o) const
+    __device__ __forceinline__ float dot(const WaveRow &o) const
     {
         float s = 0.f;
 #pragma unroll
@@ -66,7 +65,7 @@ struct FwdRow {
         if (TAIL) s = fmaf(t, o.t, s);
         return s;
     }
-    __device__ __forceinline__ void axpy(float a, const FwdRow &x)
+    __device__ __forceinline__ void axpy(float a, const WaveRow &x)
     {
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
@@ -90,6 +89,27 @@ struct FwdRow {
         }
         if (TAIL) dst[4 * WAVE * NQ + lane] = t;
     }
+    // the row to D floats in global memory; STREAM: around the caches
+    template <bool STREAM>
+    __device__ __forceinline__ void store(float *row, int D, int lane) const
+    {
+        const int C4 = TAIL ? NQ * WAVE : (D >> 2);
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            const int c = lane + WAVE * it;
+            if (c < C4) {
+                if (STREAM) st4s(row + 4 * c, q[it]);
+                else st4(row + 4 * c, q[it]);
+            }
+        }
+        if (TAIL) {
+            const int e = 4 * WAVE * NQ + lane;
+            if (e < D) {
+                if (STREAM) __builtin_nontemporal_store(t, (GLOBAL_AS float *)(row + e));
+                else row[e] = t;
+            }
+        }
+    }
     static __device__ __forceinline__ float elem(const float *row, int e) { return row[e]; }
     static __device__ __forceinline__ float elem(const bf16_t *row, int e) { return bf16_to_f32(row[e]); }
 };
@@ -105,11 +125,18 @@ struct FwdShape {
     static constexpr int unroll = regs <= 5 ? 4 : 2;
 };
 
+// rows in flight per wave in the segmented reduction
+template <int NQ, bool TAIL>
+struct SegShape {
+    static constexpr int regs = 4 * NQ + (TAIL ? 1 : 0);
+    static constexpr int unroll = regs <= 5 ? 2 * SEG_UNROLL : SEG_UNROLL;
+};
+
 // LOSS: also accumulate the loss terms (only when the caller asked for the mean loss).
 template <typename T, int NQ, bool TAIL, bool LOSS>
 __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
 {
-    typedef FwdRow<NQ, TAIL> Row;
+    typedef WaveRow<NQ, TAIL> Row;
     constexpr int UNROLL = FwdShape<NQ, TAIL>::unroll;
     __shared__ float red[WAVES_PER_BLOCK][(NQ * 4 + (TAIL ? 1 : 0)) * WAVE];
     __shared__ float lred[WAVES_PER_BLOCK];
@@ -225,7 +252,7 @@ void tn_launch_forward(const FwdArgs &a, hipStream_t st)
 
 // ---------------------------------------------------------------- segmented reduction
 // Contribution of sorted entry e: scale * row, both fetched by the wave.
-template <typename T, int ITERS, int MODE>
+template <typename T, int MODE>
 __device__ __forceinline__ void entry_source(const SegReduceArgs &a, u32 val, const T *&row,
                                              float &scale)
 {
@@ -245,9 +272,11 @@ __device__ __forceinline__ void entry_source(const SegReduceArgs &a, u32 val, co
 // tile sums the part of the row that lies inside it into a partial (part[tile][0] for a row that
 // began in an earlier tile, part[tile][1] for one that begins here), and k_segfixup chains the
 // partials in tile order.  Work per wave is bounded by 2*TILE entries whatever the skew of the ids.
-template <typename T, int ITERS, int MODE, int TILE>
+template <typename T, int NQ, bool TAIL, int MODE, int TILE>
 __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block)
 {
+    typedef WaveRow<NQ, TAIL> Row;
+    constexpr int UNROLL = SegShape<NQ, TAIL>::unroll;
     static_assert(2 * TILE <= WAVE, "a wave keeps the metadata of two tiles in its lanes");
     // the wave index is made explicitly wave-uniform so that all the control flow below is scalar
     const int tile = block * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6));
@@ -255,7 +284,6 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
     const int t0 = tile * TILE;
     if (t0 >= a.n) return;
     const int t1 = min(a.n, t0 + TILE);
-    const int C4 = a.D >> 2;
 
     // lane l holds the metadata of entry t0 + l, for this tile and the next
     const int avail = min(2 * TILE, a.n - t0);
@@ -267,7 +295,7 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
     }
     const T *row_l = nullptr;
     float scale_l = 0.f;
-    if (lane < avail) entry_source<T, ITERS, MODE>(a, val_l, row_l, scale_l);
+    if (lane < avail) entry_source<T, MODE>(a, val_l, row_l, scale_l);
 
     // heads inside the two-tile window (bit l: entry t0+l opens a row); bit `avail` closes the list
     const int seg_up = __shfl_up(seg_l, 1, WAVE);
@@ -310,52 +338,52 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
     if (a.cross && (tile % TN_SEG_XBLOCK) == 0 && tile > 0 && lane == 0)
         a.xinfo[tile / TN_SEG_XBLOCK] = (first_start < t0 && dest == 1) ? 1 : 0;
     if (e_begin >= e_end) return;
-    float4 acc[ITERS];
-    zero_row<ITERS>(acc);
+    Row acc;
+    acc.zero();
     float *part = a.part + (size_t)tile * 2 * a.D;
     int cur = rd_lane(seg_l, e_begin);
     if (e_begin > 0) {   // the first owned row begins at e_begin
         const int end = row_end(e_begin);
         dest = ((end < 0) || (end - e_begin) > TILE) ? 2 : 0;
     }
+    // a finished gradient row is next read by the table update, long after this kernel: it is written
+    // around the caches (with ordinary stores the update ran 4 % slower, paying for the write-back of
+    // these lines), while partials are read again at once
+    auto flush = [&]() {
+        if (dest == 0) acc.template store<true>(a.out_rows + (size_t)cur * a.D, a.D, lane);
+        else acc.template store<false>(dest == 1 ? part : part + a.D, a.D, lane);
+    };
 
-    for (int e0 = e_begin; e0 < e_end; e0 += SEG_UNROLL) {
-        float4 r[SEG_UNROLL][ITERS];
-        float sc[SEG_UNROLL];
-        int sg[SEG_UNROLL];
+    for (int e0 = e_begin; e0 < e_end; e0 += UNROLL) {
+        Row r[UNROLL];
+        float sc[UNROLL];
+        int sg[UNROLL];
 #pragma unroll
-        for (int x = 0; x < SEG_UNROLL; ++x) {
+        for (int x = 0; x < UNROLL; ++x) {
             const int e = e0 + x;
             if (e < e_end) {
                 sg[x] = rd_lane(seg_l, e);
                 sc[x] = rd_lane(scale_l, e);
                 const T *row = (const T *)rd_lane64((u64)row_l, e);
-                load_row<T, ITERS>(r[x], row, C4, lane);
+                r[x].load(row, a.D, lane);
             }
         }
 #pragma unroll
-        for (int x = 0; x < SEG_UNROLL; ++x) {
+        for (int x = 0; x < UNROLL; ++x) {
             const int e = e0 + x;
             if (e < e_end) {
                 if (sg[x] != cur) {   // row `cur` is complete (or its share of it): write it out
-                    float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
-                    // a finished gradient row is next read by the table update, long after this kernel:
-                    // written around the caches (with ordinary stores the update ran 4 % slower, paying
-                    // for the write-back of these lines), while partials are read again at once
-                    if (dest == 0) store_row_s<float, ITERS>(dst, acc, C4, lane);
-                    else store_row<float, ITERS>(dst, acc, C4, lane);
-                    zero_row<ITERS>(acc);
+                    flush();
+                    acc.zero();
                     cur = sg[x];
                     const int end = row_end(e);
                     dest = ((end < 0) || (end - e) > TILE) ? 2 : 0;
                 }
-                axpy_row<ITERS>(acc, sc[x], r[x]);
+                acc.axpy(sc[x], r[x]);
             }
         }
     }
-    float *dst = dest == 0 ? a.out_rows + (size_t)cur * a.D : (dest == 1 ? part : part + a.D);
-    if (dest == 0) store_row_s<float, ITERS>(dst, acc, C4, lane);
-    else store_row<float, ITERS>(dst, acc, C4, lane);
+    flush();
     // a long row begins in this tile: leave its tile for the kernel that chains the partials
     // (integer counter; the order of the list does not matter, every chain is independent)
     if (dest == 2 && lane == 0) a.long_list[atomicAdd(a.long_cnt, 1)] = tile;
@@ -369,12 +397,12 @@ struct SegReducePair {
     int blocks_in;    // workgroups of the in-side problem at the front of the grid
 };
 
-template <typename T, int ITERS, int TILE_OUT, int TILE_IN>
+template <typename T, int NQ, bool TAIL, int TILE_OUT, int TILE_IN>
 __global__ void __launch_bounds__(BLOCK) k_segreduce(SegReducePair p)
 {
     const int b = blockIdx.x;
-    if (b < p.blocks_in) segreduce_tile<float, ITERS, 1, TILE_IN>(p.in, b);
-    else segreduce_tile<T, ITERS, 0, TILE_OUT>(p.out, b - p.blocks_in);
+    if (b < p.blocks_in) segreduce_tile<float, NQ, TAIL, 1, TILE_IN>(p.in, b);
+    else segreduce_tile<T, NQ, TAIL, 0, TILE_OUT>(p.out, b - p.blocks_in);
 }
 
 // Chains the partials of long rows in tile order: one workgroup per long row (grid-strided
@@ -507,17 +535,20 @@ __global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReducePair p)
     else segfixup_rows<ITERS, TILE_OUT>(p.out, b - p.blocks_in, (int)gridDim.x - p.blocks_in, red);
 }
 
-template <typename T, int ITERS, int TILE_OUT, int TILE_IN>
+// ITERS: float4 registers per lane of a whole row (the chaining kernels' layout); TAIL: the reduction
+// holds rows as ITERS-1 float4 and one float per lane instead (dimensions just above a multiple of 256)
+template <typename T, int ITERS, bool TAIL, int TILE_OUT, int TILE_IN>
 static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
 {
+    constexpr int NQ = TAIL ? ITERS - 1 : ITERS;
     const int tiles_out = p.out.n > 0 ? (p.out.n + TILE_OUT - 1) / TILE_OUT : 0;
     const int tiles_in = p.in.n > 0 ? (p.in.n + TILE_IN - 1) / TILE_IN : 0;
     if (tiles_out <= TN_SEG_CROSS_MIN) p.out.cross = nullptr;
     if (tiles_in <= TN_SEG_CROSS_MIN) p.in.cross = nullptr;
     const int blocks_out = (tiles_out + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     p.blocks_in = (tiles_in + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    hipLaunchKernelGGL((k_segreduce<T, ITERS, TILE_OUT, TILE_IN>), dim3(p.blocks_in + blocks_out), dim3(BLOCK), 0,
-                       st, p);
+    hipLaunchKernelGGL((k_segreduce<T, NQ, TAIL, TILE_OUT, TILE_IN>), dim3(p.blocks_in + blocks_out), dim3(BLOCK),
+                       0, st, p);
     // Partials per block of tiles, for problems large enough that one row's chain could hold up the step:
     // up to TN_SEG_CROSS_MIN tiles even a row that takes every entry is walked by one workgroup in well
     // under a fifth of a millisecond, and the extra launch would cost every step several microseconds.
@@ -538,23 +569,32 @@ static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
     }
 }
 
-template <typename T, int ITERS>
+template <typename T, int ITERS, bool TAIL>
 static void launch_segreduce_t(SegReducePair &p, hipStream_t st)
 {
     const bool so = tn_seg_tile(p.out.n) == 8, si = tn_seg_tile(p.in.n) == 8;
-    if (so) si ? launch_segreduce_i<T, ITERS, 8, 8>(p, st) : launch_segreduce_i<T, ITERS, 8, 32>(p, st);
-    else si ? launch_segreduce_i<T, ITERS, 32, 8>(p, st) : launch_segreduce_i<T, ITERS, 32, 32>(p, st);
+    if (so) si ? launch_segreduce_i<T, ITERS, TAIL, 8, 8>(p, st) : launch_segreduce_i<T, ITERS, TAIL, 8, 32>(p, st);
+    else si ? launch_segreduce_i<T, ITERS, TAIL, 32, 8>(p, st) : launch_segreduce_i<T, ITERS, TAIL, 32, 32>(p, st);
 }
 
 template <typename T>
 static void launch_segreduce_d(SegReducePair &p, int D, hipStream_t st)
 {
     const int iters = (D / 4 + WAVE - 1) / WAVE;
+    const int rest = D - (iters - 1) * 4 * WAVE;   // elements in the last float4 register of a lane's row
+    if (iters >= 2 && rest <= WAVE) {              // a short tail: one float per lane
+        switch (iters) {
+        case 2: launch_segreduce_t<T, 2, true>(p, st); break;
+        case 3: launch_segreduce_t<T, 3, true>(p, st); break;
+        default: launch_segreduce_t<T, 4, true>(p, st); break;
+        }
+        return;
+    }
     switch (iters) {
-    case 1: launch_segreduce_t<T, 1>(p, st); break;
-    case 2: launch_segreduce_t<T, 2>(p, st); break;
-    case 3: launch_segreduce_t<T, 3>(p, st); break;
-    default: launch_segreduce_t<T, 4>(p, st); break;
+    case 1: launch_segreduce_t<T, 1, false>(p, st); break;
+    case 2: launch_segreduce_t<T, 2, false>(p, st); break;
+    case 3: launch_segreduce_t<T, 3, false>(p, st); break;
+    default: launch_segreduce_t<T, 4, false>(p, st); break;
     }
 }
 
