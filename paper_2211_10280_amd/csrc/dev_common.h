@@ -113,6 +113,24 @@ __device__ __forceinline__ void store_row_s(T *row, const float4 (&r)[ITERS], in
         if (c < C4) st4s(row + 4 * c, r[it]);
     }
 }
+// Streaming load of a whole row whose ends need not fall on cache-line borders: the 128-byte lines
+// that the row fills completely go around the caches, the (at most two) lines it shares with its
+// neighbours in memory go through them, so that the neighbour finds them there.
+template <typename T, int ITERS>
+__device__ __forceinline__ void load_row_edges(float4 (&r)[ITERS], const T *row, int C4, int lane)
+{
+    const uintptr_t lo = (uintptr_t)row, hi = lo + (size_t)C4 * 4 * sizeof(T);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        r[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < C4) {
+            const uintptr_t line = (uintptr_t)(row + 4 * c) & ~(uintptr_t)127;
+            if (line >= lo && line + 128 <= hi) r[it] = ld4s(row + 4 * c);
+            else r[it] = ld4(row + 4 * c);
+        }
+    }
+}
 template <int ITERS>
 __device__ __forceinline__ void zero_row(float4 (&r)[ITERS])
 {
