@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--no-prefetch", action="store_true",
                     help="every step self-contained (default: the next mini-batch is handed to tensair_prefetch "
                          "after each step, as it would be waiting in the worker's input queue)")
+    ap.add_argument("--row-stride", type=int, default=None,
+                    help="elements between table rows (default: dim; a multiple of 32 fp32 / 64 bf16 elements "
+                         "starts every row on a 128-byte line)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
     ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine"], default="step",
                     help="step: the worker step (the metric); the others time one of the further operations on its own")
@@ -80,7 +83,7 @@ def main():
     if args.op != "step":
         return bench_streaming(args, cfg)
 
-    worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch)
+    worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch, row_stride=args.row_stride)
     model = worker.model
     theta0 = (model.w_in.clone(), model.w_out.clone())
     D, e = cfg.dim, cfg.elem_bytes
@@ -199,7 +202,8 @@ def main():
         "config": {"workload": cfg.name, "vocab": cfg.vocab, "dim": cfg.dim, "window": cfg.window,
                    "negatives": cfg.negatives, "batch_centers": cfg.batch, "peers": K,
                    "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S,
-                   "next_batch_prefetch": not args.no_prefetch},
+                   "next_batch_prefetch": not args.no_prefetch,
+                   "row_stride": model.cfg.row_stride},
         "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
         "measured_copy_GBps": copy_GBps,
         "step_algorithmic_bytes": step_bytes / S,

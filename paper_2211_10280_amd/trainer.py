@@ -23,7 +23,8 @@ from . import workload as W
 
 
 class DasgdWorker:
-    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True):
+    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True,
+                 row_stride=None):
         self.cfg = cfg
         self.prefetch = prefetch     # announce coming mini-batches with tensair_prefetch
         self.announced = -1          # last step whose mini-batch has been announced
@@ -31,12 +32,13 @@ class DasgdWorker:
         dt = B.F32 if cfg.dtype == "f32" else B.BF16
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
         self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
-                             max(cfg.peers, 0), cfg.seed, counts, worker_id=0, device=device)
+                             max(cfg.peers, 0), cfg.seed, counts, worker_id=0, row_stride=row_stride,
+                             device=device)
         # a second handle computes the peers' gradients on snapshots (its tables are rebound per call)
         self.peer_model = None
         if cfg.peers > 0:
             self.peer_model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch, 0,
-                                      cfg.seed, counts, worker_id=1,
+                                      cfg.seed, counts, worker_id=1, row_stride=row_stride,
                                       tables=(self.model.w_in, self.model.w_out), device=device)
         self.own = self.model.grad_buffers()
         self.peer_bufs = [self.model.grad_buffers() for _ in range(cfg.peers)]

@@ -188,8 +188,8 @@ def _rand_sparse(rng, V, D, U):
                                               (513, 512, 512, 31, True), (2000, 64, 64, 4, False),
                                               (63, 8, 8, 2, True),
                                               # tables beyond 1 GiB: the variant that goes around the caches, rows
-                                              # that do not end on cache-line borders
-                                              (1_000_003, 300, 300, 2, True)])
+                                              # that do not end on cache-line borders, and rows padded to them
+                                              (1_000_003, 300, 300, 2, True), (1_000_003, 300, 320, 2, True)])
 def test_dasgd_apply_parity(dtype, V, D, stride, K, own):
     _say("apply", dtype, V, D, stride, K, own)
     bd, od, _, _ = DT[dtype]
