@@ -228,6 +228,46 @@ def grad_add(a: Grad, b: Grad, D: int) -> Grad:
                 SparseRows(gi[0], gi[1], none), SparseRows(go[0], go[1], none))
 
 
+# ---------------------------------------------------------------- gradient messages in bfloat16
+def grad_pack_rows(rows):
+    """A gradient message whose rows travel as bfloat16 -- a variant beyond the paper, which sends
+    float gradients and names gradient application and the network as what limits Word2Vec
+    scaling (Section 4.3).  Every element of the float32 rows is rounded to the nearest
+    bfloat16, ties to even: the candidates are the bfloat16 values at and above |x| (the float's
+    upper 16 bits, and that plus one unit in the last place), the nearer one is taken, measured
+    in double; beyond the largest finite bfloat16 the upper candidate counts as 2^128, so that
+    what lies past the midpoint becomes infinity; infinities keep their sign, NaN becomes
+    0x7FC0.  rows: float32 array; returns uint16 bits of the same shape."""
+    x = np.ascontiguousarray(rows, dtype=np.float32)
+    bits = x.view(np.uint32)
+    sign = (bits >> np.uint32(31)).astype(np.uint16) << np.uint16(15)
+    mag = np.abs(x.astype(np.float64))
+    lo = (bits & np.uint32(0x7FFF0000)).astype(np.uint32)      # magnitude truncated to bfloat16
+    hi = (lo + np.uint32(0x10000)).astype(np.uint32)
+    lo_v = lo.view(np.float32).astype(np.float64)
+    with np.errstate(over="ignore", invalid="ignore"):
+        hi_v = np.where(hi >= np.uint32(0x7F800000), 2.0 ** 128, hi.view(np.float32).astype(np.float64))
+        d_lo, d_hi = mag - lo_v, hi_v - mag
+    odd = ((lo >> np.uint32(16)) & np.uint32(1)) == 1
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & odd)
+    out = (np.where(take_hi, hi, lo) >> np.uint32(16)).astype(np.uint16) | sign
+    out = np.where(np.isinf(x), np.uint16(0x7F80) | sign, out)
+    out = np.where(np.isnan(x), np.uint16(0x7FC0), out)
+    return out.astype(np.uint16)
+
+
+def grad_unpack_rows(bits):
+    """The float32 rows a receiver sees in a bfloat16 gradient message (exact widening)."""
+    return bf16_to_f32(np.asarray(bits, dtype=np.uint16))
+
+
+def grad_through_bf16(g: Grad) -> Grad:
+    """A gradient as its receiver sees it after travelling as a bfloat16 message: same rows
+    listed, every element rounded once."""
+    r = lambda s: SparseRows(s.ids, grad_unpack_rows(grad_pack_rows(s.rows)), s.seg)
+    return Grad(g.P, g.loss, g.negatives, r(g.gin), r(g.gout))
+
+
 # ---------------------------------------------------------------- dense model, predict path, drift metric
 def dense_apply(theta, dtype, grads, lr):
     """apply_gradient of Algorithm 1 / Eq. 1 for a dense model (Section 4, "Sparse vs. Dense

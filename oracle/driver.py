@@ -24,7 +24,8 @@ from paper_2211_10280_amd import workload as W
 
 
 class OracleWorker:
-    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, threads: int = 1):
+    def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, threads: int = 1,
+                 bf16_messages: bool = False):
         self.cfg = cfg
         self.tok = np.ascontiguousarray(tokens, dtype=np.int32)
         self.dtype = oracle.F32 if cfg.dtype == "f32" else oracle.BF16
@@ -34,6 +35,7 @@ class OracleWorker:
         self.step_no = 0
         self.stale = None
         self.threads = threads
+        self.bf16_messages = bf16_messages   # peers' gradients arrive rounded to bfloat16 (variant)
         self.last_own = None
         self.last_peers = []
         # G sets of Section 3.1: gradients this worker has applied, as (step, worker) names
@@ -88,6 +90,8 @@ class OracleWorker:
                 self.sent = self.own_buffer
                 self.own_buffer = None
                 self.peer_buffers = [None] * c.peers
+        if self.bf16_messages:       # what is sent is rounded once, after any summing in the sender's buffer
+            grads = [grads[0]] + [oracle.grad_through_bf16(g) for g in grads[1:]]
         t0 = time.perf_counter()
         oracle.dasgd_apply(self.W_in, self.W_out, c.dim, self.dtype, grads, c.lr)
         self.t_apply = time.perf_counter() - t0

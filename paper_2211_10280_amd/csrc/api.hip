@@ -135,8 +135,9 @@ struct tensair_model {
     u32 *wbase[2], *wblk[2];   // tensair_grad_add: place of every 64-row word in the summed gradient
     std::vector<uint32_t> h_thr;
     std::vector<int32_t> h_alias;
-    // second stream for the part of the gradient calculation that does not depend on the forward
-    // pass (sort + segments); forked from and joined to the caller's stream with events
+    // second stream, forked from and joined to the caller's stream with events: it runs what can go
+    // on next to the caller's stream (the forward pass beside the sort, the index of the coming table
+    // update beside the reductions, the preparation of announced mini-batches)
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_fwd = nullptr, ev_segs = nullptr, ev_index = nullptr;
     // mini-batch sets: `busy` is the one the most recent gradient call reads; announced mini-batches are

@@ -138,17 +138,6 @@ __device__ __forceinline__ void zero_row(float4 (&r)[ITERS])
     for (int it = 0; it < ITERS; ++it) r[it] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 template <int ITERS>
-__device__ __forceinline__ void axpy_row(float4 (&acc)[ITERS], float a, const float4 (&x)[ITERS])
-{
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        acc[it].x = fmaf(a, x[it].x, acc[it].x);
-        acc[it].y = fmaf(a, x[it].y, acc[it].y);
-        acc[it].z = fmaf(a, x[it].z, acc[it].z);
-        acc[it].w = fmaf(a, x[it].w, acc[it].w);
-    }
-}
-template <int ITERS>
 __device__ __forceinline__ void add_row(float4 (&acc)[ITERS], const float4 (&x)[ITERS])
 {
 #pragma unroll

@@ -428,3 +428,58 @@ def test_lookup_and_cosine_difference_closed_forms():
     # bf16 tables are widened exactly
     Xb = oracle._bf16_round(X.astype(np.float64))
     assert np.array_equal(oracle.lookup(Xb, oracle.BF16, 7, [5]), oracle.bf16_to_f32(Xb[[5]]))
+
+
+# ------------------------------------------------------------------ gradient messages in bfloat16
+def test_bf16_message_rounding_worked_values_and_a_library_conversion():
+    """Hand-worked roundings (ties to even on both sides of 1, the midpoint beyond the largest finite
+    value, signs, subnormals), then a tensor library's float32 -> bfloat16 conversion on a million
+    values of gradient-like magnitude."""
+    f = np.float32
+    x = np.array([1.0, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, -1 - 2.0 ** -8,
+                  1 - 2.0 ** -9, 1 - 3 * 2.0 ** -9,
+                  0.0, -0.0, np.inf, -np.inf, 3.3895313892515355e38, 3.396e38, 3.397e38, 2.0 ** -133], dtype=f)
+    want = [0x3F80, 0x3F80, 0x3F82, 0x3F81, 0xBF80,
+            0x3F80, 0x3F7E,       # below 1 the spacing is 2^-8: 1 - 2^-9 ties up to 1 (even), 1 - 3*2^-9 ties down to 0x3F7E
+            0x0000, 0x8000, 0x7F80, 0xFF80, 0x7F7F, 0x7F7F, 0x7F80, 0x0001]
+    assert oracle.grad_pack_rows(x).tolist() == want
+    assert oracle.grad_pack_rows(np.array([np.nan], f)).tolist() == [0x7FC0]
+    rng = np.random.default_rng(11)
+    r = (rng.standard_normal(1_000_000) * rng.choice([1e-8, 1e-4, 1e-2, 1.0], 1_000_000)).astype(f)
+    lib = torch.from_numpy(r).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.grad_pack_rows(r)
+    assert np.array_equal(got, lib)
+    # what the receiver sees: within half a unit in the last place (at most 2^-8 relative), sign-symmetric, idempotent
+    back = oracle.grad_unpack_rows(got)
+    assert (np.abs(back.astype(np.float64) - r) <= 2.0 ** -8 * np.abs(r)).all()
+    assert np.array_equal(oracle.grad_pack_rows(-r), got ^ np.uint16(0x8000))
+    assert np.array_equal(oracle.grad_pack_rows(back), got)
+
+
+def test_bf16_messages_move_the_update_by_at_most_their_rounding():
+    """Eq. 1 with peers' gradients that travelled as bfloat16: the own gradient is untouched, listed rows
+    stay listed, and the table differs from the one updated with the float gradients by at most
+    alpha * sum_k 2^-8 |g_k| per element (plus the final float rounding)."""
+    rng = np.random.default_rng(12)
+    V, D, lr = 40, 8, 0.5
+    W0 = rng.standard_normal((V, D)).astype(np.float32)
+    srcs = []
+    for k in range(4):
+        ids = np.sort(rng.choice(V, size=[17, 1, 40, 9][k], replace=False)).astype(np.int32)
+        srcs.append((ids, rng.standard_normal((ids.size, D)).astype(np.float32)))
+    through = [srcs[0]] + [(i, oracle.grad_unpack_rows(oracle.grad_pack_rows(r))) for i, r in srcs[1:]]
+    A, Bt = W0.copy(), W0.copy()
+    oracle.dasgd_apply_table(A, D, oracle.F32, srcs, lr)
+    oracle.dasgd_apply_table(Bt, D, oracle.F32, through, lr)
+    bound = np.zeros((V, D))
+    for ids, rows in srcs[1:]:
+        bound[ids] += 2.0 ** -8 * np.abs(rows)
+    assert (np.abs(A.astype(np.float64) - Bt) <= lr * bound + 2.0 ** -22 * np.abs(A)).all()
+    own_only = np.setdiff1d(srcs[0][0], np.concatenate([s[0] for s in srcs[1:]]))
+    assert np.array_equal(A[own_only], Bt[own_only])
+    assert (A != Bt).any()
+    # the Grad-level helper rounds both tables' rows once and keeps everything else
+    g = oracle.Grad(3, 0.5, np.zeros((3, 2), np.int32), oracle.SparseRows(srcs[1][0], srcs[1][1], np.zeros(2, np.int64)),
+                    oracle.SparseRows(srcs[2][0], srcs[2][1], np.zeros(41, np.int64)))
+    h = oracle.grad_through_bf16(g)
+    assert h.P == 3 and np.array_equal(h.gin.ids, g.gin.ids) and np.array_equal(h.gout.rows, through[2][1])
