@@ -53,7 +53,10 @@ def main():
                     help="elements between table rows (default: dim; a multiple of 32 fp32 / 64 bf16 elements "
                          "starts every row on a 128-byte line)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
-    ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine"], default="step",
+    ap.add_argument("--peer-payload", choices=["f32", "bf16"], default="f32",
+                    help="f32: the peers' gradients as the paper sends them (the metric); bf16: as bfloat16 messages "
+                         "(tensair_grad_pack / tensair_step_packed, a variant)")
+    ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine", "grad_pack"], default="step",
                     help="step: the worker step (the metric); the others time one of the further operations on its own")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -81,12 +84,14 @@ def main():
     if args.op == "grad_add":
         return bench_grad_add(args, cfg, tok, counts)
     if args.op != "step":
-        return bench_streaming(args, cfg)
+        return bench_streaming(args, cfg, tok, counts)
 
-    worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch, row_stride=args.row_stride)
+    worker = DasgdWorker(cfg, tok, counts, prefetch=not args.no_prefetch, row_stride=args.row_stride,
+                         bf16_messages=args.peer_payload == "bf16")
     model = worker.model
     theta0 = (model.w_in.clone(), model.w_out.clone())
     D, e = cfg.dim, cfg.elem_bytes
+    peer_elem = 2 if args.peer_payload == "bf16" else 4
 
     # ---- recording pass: peers of every step, algorithmic bytes
     stored, bytes_grad, bytes_apply, pairs = [], [], [], []
@@ -95,7 +100,7 @@ def main():
         compact = []
         for pb in peers:
             ui, uo = pb.sizes()
-            cb = B.GradBuffers(ui, uo, D)
+            cb = type(pb)(ui, uo, D)
             cb.in_ids[:ui].copy_(pb.in_ids[:ui]); cb.in_rows[:ui].copy_(pb.in_rows[:ui])
             cb.out_ids[:uo].copy_(pb.out_ids[:uo]); cb.out_rows[:uo].copy_(pb.out_rows[:uo])
             cb.n_rows.copy_(pb.n_rows)
@@ -107,9 +112,9 @@ def main():
         srcs_out = [worker.own.out_ids[:uo]] + [c.out_ids[: c.cap_out] for c in compact]
         r_in = int(torch.unique(torch.cat(srcs_in)).numel())
         r_out = int(torch.unique(torch.cat(srcs_out)).numel())
-        rows_all = sum(int(x.numel()) for x in srcs_in) + sum(int(x.numel()) for x in srcs_out)
+        rows_peers = sum(int(x.numel()) for x in srcs_in[1:]) + sum(int(x.numel()) for x in srcs_out[1:])
         bytes_grad.append((ui + uo) * D * e + (ui + uo) * D * 4)
-        bytes_apply.append(rows_all * D * 4 + 2 * (r_in + r_out) * D * e)
+        bytes_apply.append((ui + uo) * D * 4 + rows_peers * D * peer_elem + 2 * (r_in + r_out) * D * e)
         pairs.append(model.pair_count(cfg.tokens, begin, n))
     model.status()
     torch.cuda.synchronize()
@@ -162,7 +167,7 @@ def main():
     achieved = apply_bytes_per_launch / apply_avg_s
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}{'_bf16_messages' if peer_elem == 2 else ''}.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("k_apply_hbm_bytes_per_step") / (n_launch // S)
@@ -197,13 +202,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if cfg.dtype == "f32" else "bf16 tables, f32 accumulation",
+        "dtype": ("f32" if cfg.dtype == "f32" else "bf16 tables, f32 accumulation") +
+                 (", peer gradients as bf16 messages" if peer_elem == 2 else ""),
         "data": "synthetic",
         "config": {"workload": cfg.name, "vocab": cfg.vocab, "dim": cfg.dim, "window": cfg.window,
                    "negatives": cfg.negatives, "batch_centers": cfg.batch, "peers": K,
                    "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S,
                    "next_batch_prefetch": not args.no_prefetch,
-                   "row_stride": model.cfg.row_stride},
+                   "row_stride": model.cfg.row_stride, "peer_payload": args.peer_payload},
         "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
         "measured_copy_GBps": copy_GBps,
         "step_algorithmic_bytes": step_bytes / S,
@@ -222,7 +228,7 @@ def main():
         from oracle.driver import OracleWorker
 
         t0 = time.perf_counter()
-        ow = OracleWorker(cfg, tok, counts, threads=1)
+        ow = OracleWorker(cfg, tok, counts, threads=1, bf16_messages=peer_elem == 2)
         n_cpu = {1: 157, 2: 12, 3: 4, 4: 1, 5: 1}[cfg.idx]
         cpu_t, p_cpu = 0.0, 0
         for t in range(n_cpu):
@@ -324,8 +330,9 @@ def bench_grad_add(args, cfg, tok, counts):
     print(json.dumps(out_json), flush=True)
 
 
-def bench_streaming(args, cfg):
-    """dense_apply: theta of V*D elements, K+1 gradient blocks; lookup: 1 M random words; cosine: two tables."""
+def bench_streaming(args, cfg, tok, counts):
+    """dense_apply: theta of V*D elements, K+1 gradient blocks; lookup: 1 M random words; cosine: two tables;
+    grad_pack: the gradient of the workload's first mini-batch into a bfloat16 message."""
     import numpy as np
     import torch
 
@@ -375,6 +382,27 @@ def bench_streaming(args, cfg):
             t0 = time.perf_counter()
             oracle.lookup(Wn, odt, D, idn)
             return n / (time.perf_counter() - t0), "the same lookup, once"
+    elif args.op == "grad_pack":
+        from paper_2211_10280_amd import workload as W
+
+        m = B.Model(V, D, B.F32 if cfg.dtype == "f32" else B.BF16, cfg.window, cfg.negatives, cfg.batch, 0, cfg.seed, counts)
+        m.w_out.copy_(m.w_in)     # W_out away from zero so that both sides carry non-trivial rows
+        dtok = torch.from_numpy(np.ascontiguousarray(tok, dtype=np.int32)).cuda()
+        g, msg = m.grad_buffers(), m.packed_buffers()
+        b0 = W.worker_batch(cfg, 0, 0)
+        m.sgns_grad(dtok, b0[0], b0[1], b0[2], g)
+        rows = sum(g.sizes())
+        call = lambda: m.grad_pack(g, msg)
+        alg = rows * (D * 4 + D * 2 + 8)
+        units, unit, kernel = rows, "rows/s", "k_grad_pack"
+        what = {"rows": rows, "dim": D}
+
+        def cpu():
+            (_, ri), (_, ro) = g.to_host()
+            t0 = time.perf_counter()
+            oracle.grad_pack_rows(ri)
+            oracle.grad_pack_rows(ro)
+            return rows / (time.perf_counter() - t0), "the same gradient, once"
     else:
         a = (torch.randn((V, D), device="cuda", generator=gen) * 0.1).to(tdt)
         b = (a.float() + torch.randn((V, D), device="cuda", generator=gen) * 0.02).to(tdt)
@@ -420,7 +448,8 @@ def bench_streaming(args, cfg):
     out_json = {
         "metric": {"dense_apply": "dense-model gradient application (Eq. 1 on every parameter)",
                    "lookup": "embedding lookup (predict path)",
-                   "cosine": "cosine difference between two embedding tables"}[args.op],
+                   "cosine": "cosine difference between two embedding tables",
+                   "grad_pack": "sparse gradient into a bfloat16 message"}[args.op],
         "value": units / (elapsed / S), "unit": unit, "n_gpus": 1, "steps": S, "warmup": Wm,
         "ms_per_step": elapsed / S * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg.dtype == "f32" else "bf16 tables, f32 arithmetic", "data": "synthetic",

@@ -12,6 +12,8 @@
  *   apply_gradient for a dense model                 -> tensair_dense_apply
  *   predict(msg) for an embedding model              -> tensair_lookup
  *   cosine difference of two embedding tables (Section 4.4) -> tensair_cosine_difference
+ *   a gradient message with bfloat16 rows (a variant beyond the paper) -> tensair_grad_pack,
+ *       tensair_dasgd_apply_packed, tensair_step_packed
  *
  * Conventions for every call
  *   - Plain C ABI.  Pointers marked DEVICE point to GPU memory owned by the caller;
@@ -83,6 +85,20 @@ typedef struct {
 typedef struct {
     tensair_sparse_rows in, out;
 } tensair_sparse_grad;
+
+/* The same message with its rows rounded to bfloat16: half the bytes on the wire and in the
+ * receiver's gradient application.  Same layout; row_grads is [capacity][dim] bfloat16 bits, 16-byte
+ * aligned.  Written by tensair_grad_pack, read by tensair_dasgd_apply_packed / tensair_step_packed. */
+typedef struct {
+    int64_t capacity;
+    int32_t *n_rows;
+    int32_t *row_ids;
+    uint16_t *row_grads;
+} tensair_packed_rows;
+
+typedef struct {
+    tensair_packed_rows in, out;
+} tensair_packed_grad;
 
 /* Bytes of DEVICE workspace tensair_model_init needs for `cfg` (0 if cfg is invalid). */
 size_t tensair_workspace_bytes(const tensair_config *cfg);
@@ -194,6 +210,27 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
                  int32_t n_peers, float lr, tensair_sparse_grad *own_out, float *mean_loss,
                  void *stream);
 
+/* A variant the paper leaves open.  Section 4.3 finds that with more than three GPUs Word2Vec training
+ * is limited by gradient application, which is not distributed, and every gradient message of
+ * Algorithm 1 is broadcast to all other instances; the paper's remedy is maxGradBuffer.  Sending
+ * the rows as bfloat16 halves both costs at the price of one rounding per element:
+ * tensair_grad_pack turns a gradient into such a message -- *n_rows and the row ids are copied,
+ * every element of the rows is rounded to the nearest bfloat16, ties to even (NaN becomes 0x7FC0,
+ * values beyond the largest finite bfloat16 become infinity).  out needs capacities >= g's row counts
+ * (else the message is cut off there and tensair_status reports TENSAIR_EDATA) and must not share
+ * buffers with g.
+ * tensair_dasgd_apply_packed is tensair_dasgd_apply with the peers' gradients given as such
+ * messages: W[r] <- W[r] - lr * (own[r] + widen(peer_1[r]) + ... + widen(peer_K[r])), the own
+ * gradient still fp32, the sum in fp32 in that order, one rounding on store.
+ * tensair_step_packed is tensair_step with packed peers; own_out stays fp32 (pack it to send it). */
+int tensair_grad_pack(tensair_model *m, const tensair_sparse_grad *g, tensair_packed_grad *out, void *stream);
+int tensair_dasgd_apply_packed(tensair_model *m, const tensair_sparse_grad *own,
+                               const tensair_packed_grad *peers, int32_t n_peers, float lr, void *stream);
+int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                        int32_t n_centers, uint32_t epoch, const tensair_packed_grad *peers,
+                        int32_t n_peers, float lr, tensair_sparse_grad *own_out, float *mean_loss,
+                        void *stream);
+
 /* Announces a coming mini-batch, so that the part of its tensair_sgns_grad / tensair_step
  * call that does not depend on the tables -- pair enumeration, negatives, sort by row id,
  * segments, unique row ids -- is prepared ahead of time on the library's own stream, next to
@@ -225,7 +262,8 @@ int tensair_status(tensair_model *m, void *stream);
  * (tag, milliseconds) records since the previous read and returns their number (negative =
  * error).  Tags: 1 keys+negatives, 2 forward, 3 sort, 4 segments, 5 reduce W_in side,
  * 6 reduce W_out side, 8 apply index, 9 apply table update, 11 index and scan of
- * tensair_grad_add, 12 its row kernel (level 1 also brackets that one); a tag's time runs from
+ * tensair_grad_add, 12 its row kernel (level 1 also brackets that one), 14 the kernel of
+ * tensair_grad_pack (level 1 too); a tag's time runs from
  * the previous event to its own.  At most 65536 events are kept between reads. */
 int tensair_profile(tensair_model *m, int level);
 int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max_records);

@@ -26,11 +26,11 @@ SYMBOLS = [
     "tensair_dasgd_apply", "tensair_step", "tensair_status", "tensair_model_destroy",
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
     "tensair_prefetch", "tensair_grad_add", "tensair_dense_apply", "tensair_lookup",
-    "tensair_cosine_difference",
+    "tensair_cosine_difference", "tensair_grad_pack", "tensair_dasgd_apply_packed", "tensair_step_packed",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
-                8: "apply_index", 9: "apply_update", 11: "add_index", 12: "add_rows"}
+                8: "apply_index", 9: "apply_update", 11: "add_index", 12: "add_rows", 14: "pack"}
 
 
 class TensairError(RuntimeError):
@@ -101,6 +101,13 @@ def lib():
         L.tensair_lookup.restype = C.c_int
         L.tensair_cosine_difference.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
         L.tensair_cosine_difference.restype = C.c_int
+        # a packed gradient has the layout of a sparse one (its rows are bfloat16 instead of fp32)
+        L.tensair_grad_pack.argtypes = [vp, C.POINTER(SparseGrad), C.POINTER(SparseGrad), vp]
+        L.tensair_grad_pack.restype = C.c_int
+        L.tensair_dasgd_apply_packed.argtypes = L.tensair_dasgd_apply.argtypes
+        L.tensair_dasgd_apply_packed.restype = C.c_int
+        L.tensair_step_packed.argtypes = L.tensair_step.argtypes
+        L.tensair_step_packed.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
@@ -135,13 +142,15 @@ def _stream(stream=None):
 class GradBuffers:
     """Device memory of one tensair_sparse_grad (caller-owned, as the ABI asks)."""
 
+    ROWS = torch.float32
+
     def __init__(self, cap_in: int, cap_out: int, dim: int, device="cuda"):
         self.dim = dim
         self.n_rows = torch.zeros(2, dtype=torch.int32, device=device)     # [in, out]
         self.in_ids = torch.empty(max(cap_in, 1), dtype=torch.int32, device=device)
-        self.in_rows = torch.empty((max(cap_in, 1), dim), dtype=torch.float32, device=device)
+        self.in_rows = torch.empty((max(cap_in, 1), dim), dtype=self.ROWS, device=device)
         self.out_ids = torch.empty(max(cap_out, 1), dtype=torch.int32, device=device)
-        self.out_rows = torch.empty((max(cap_out, 1), dim), dtype=torch.float32, device=device)
+        self.out_rows = torch.empty((max(cap_out, 1), dim), dtype=self.ROWS, device=device)
         self.cap_in, self.cap_out = cap_in, cap_out
         self.c = SparseGrad()
         self.c.in_ = SparseRows(cap_in, self.n_rows.data_ptr(), self.in_ids.data_ptr(), self.in_rows.data_ptr())
@@ -168,6 +177,28 @@ class GradBuffers:
             self.in_rows[:ui] = torch.from_numpy(np.ascontiguousarray(rows_in, dtype=np.float32)).to(self.in_ids.device)
         if uo:
             self.out_rows[:uo] = torch.from_numpy(np.ascontiguousarray(rows_out, dtype=np.float32)).to(self.in_ids.device)
+        self.n_rows.copy_(torch.tensor([ui, uo], dtype=torch.int32))
+
+
+class PackedBuffers(GradBuffers):
+    """Device memory of one tensair_packed_grad: the same, with bfloat16 rows (kept as int16 bits)."""
+    ROWS = torch.int16
+
+    def to_host(self):
+        (ii, ri), (io, ro) = super().to_host()
+        return (ii, ri.view(np.uint16)), (io, ro.view(np.uint16))
+
+    def load(self, ids_in, bits_in, ids_out, bits_out):
+        """Fill from host arrays; the rows are uint16 bfloat16 bits."""
+        ui, uo = len(ids_in), len(ids_out)
+        assert ui <= self.cap_in and uo <= self.cap_out
+        dev = self.in_ids.device
+        self.in_ids[:ui] = torch.from_numpy(np.ascontiguousarray(ids_in, dtype=np.int32)).to(dev)
+        self.out_ids[:uo] = torch.from_numpy(np.ascontiguousarray(ids_out, dtype=np.int32)).to(dev)
+        if ui:
+            self.in_rows[:ui] = torch.from_numpy(np.ascontiguousarray(bits_in, dtype=np.uint16).view(np.int16)).to(dev)
+        if uo:
+            self.out_rows[:uo] = torch.from_numpy(np.ascontiguousarray(bits_out, dtype=np.uint16).view(np.int16)).to(dev)
         self.n_rows.copy_(torch.tensor([ui, uo], dtype=torch.int32))
 
 
@@ -242,6 +273,24 @@ def tensair_step(h, tokens, center_begin: int, n_centers: int, epoch: int, peers
     _check(lib().tensair_step(h, _ptr(tokens), tokens.numel(), center_begin, n_centers, epoch, arr,
                               len(peers), C.c_float(lr), C.byref(own_out.c), _ptr(mean_loss),
                               _stream(stream)))
+
+
+def tensair_grad_pack(h, g: GradBuffers, out: PackedBuffers, stream=None):
+    _check(lib().tensair_grad_pack(h, C.byref(g.c), C.byref(out.c), _stream(stream)))
+
+
+def tensair_dasgd_apply_packed(h, own, peers, lr: float, stream=None):
+    arr = _peer_array(peers)
+    _check(lib().tensair_dasgd_apply_packed(h, C.byref(own.c) if own is not None else None, arr, len(peers),
+                                            C.c_float(lr), _stream(stream)))
+
+
+def tensair_step_packed(h, tokens, center_begin: int, n_centers: int, epoch: int, peers, lr: float,
+                        own_out: GradBuffers, mean_loss=None, stream=None):
+    arr = _peer_array(peers)
+    _check(lib().tensair_step_packed(h, _ptr(tokens), tokens.numel(), center_begin, n_centers, epoch, arr,
+                                     len(peers), C.c_float(lr), C.byref(own_out.c), _ptr(mean_loss),
+                                     _stream(stream)))
 
 
 def tensair_prefetch(h, tokens, center_begin: int, n_centers: int, epoch: int, stream=None):
@@ -342,6 +391,20 @@ class Model:
 
     def step(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
         tensair_step(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+
+    def grad_pack(self, g, out):
+        tensair_grad_pack(self.h, g, out)
+
+    def dasgd_apply_packed(self, own, peers, lr):
+        tensair_dasgd_apply_packed(self.h, own, peers, lr)
+
+    def step_packed(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
+        tensair_step_packed(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+
+    def packed_buffers(self, n_centers=None) -> PackedBuffers:
+        n = self.cfg.max_centers if n_centers is None else n_centers
+        return PackedBuffers(tensair_capacity_in(self.cfg, n), tensair_capacity_out(self.cfg, n),
+                             self.cfg.dim, self.device)
 
     def lookup(self, table, ids, out):
         tensair_lookup(self.h, table, ids, out)

@@ -266,13 +266,14 @@ bool build_alias(const uint64_t *counts, i64 V, std::vector<uint32_t> &thr,
 
 // Stage tags of tensair_profile_read.  A tag's duration runs from the previous mark to its own.
 enum { PF_BEGIN_GRAD = 0, PF_KEYS, PF_FORWARD, PF_SORT, PF_SEGMENTS, PF_REDUCE_IN, PF_REDUCE_OUT,
-       PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE, PF_BEGIN_ADD, PF_ADD_INDEX, PF_ADD_ROWS };
+       PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE, PF_BEGIN_ADD, PF_ADD_INDEX, PF_ADD_ROWS,
+       PF_BEGIN_PACK, PF_PACK };
 
 void mark(tensair_model *m, int tag, hipStream_t st)
 {
     if (m->prof_level == 0) return;
     if (m->prof_level == 1 && tag != PF_APPLY_INDEX && tag != PF_APPLY_UPDATE && tag != PF_ADD_INDEX &&
-        tag != PF_ADD_ROWS)
+        tag != PF_ADD_ROWS && tag != PF_BEGIN_PACK && tag != PF_PACK)
         return;
     if (m->prof_marks.size() >= 65536) return;
     hipEvent_t ev;
@@ -298,6 +299,24 @@ int check_rows(const tensair_sparse_rows &r, i64 need, const char *what)
         return fail(TENSAIR_ECAPACITY, "%s: capacity %lld < %lld rows required", what,
                     (long long)r.capacity, (long long)need);
     if (r.capacity > 0x7FFFFFFFLL) return fail(TENSAIR_EINVAL, "%s: capacity too large", what);
+    return TENSAIR_OK;
+}
+
+// One source of the table update: the two tables' rows of a gradient (fp32) or of a bfloat16 message.
+template <typename Grad>
+int fill_apply_src(ApplyArgs &a, int k, const Grad *g, const char *what)
+{
+    for (int t = 0; t < 2; ++t) {
+        const auto &r = t ? g->out : g->in;
+        if (!r.n_rows || !r.row_ids || !r.row_grads) return fail(TENSAIR_EINVAL, "%s: NULL pointer", what);
+        if (r.capacity < 0 || r.capacity > 0x7FFFFFFFLL) return fail(TENSAIR_EINVAL, "%s: bad capacity", what);
+        if (((uintptr_t)r.row_grads & 15) || ((uintptr_t)r.row_ids & 3) || ((uintptr_t)r.n_rows & 3))
+            return fail(TENSAIR_EINVAL, "%s: rows must be 16-byte aligned, ids and counts 4-byte aligned", what);
+        a.src[t][k].ids = r.row_ids;
+        a.src[t][k].rows = r.row_grads;
+        a.src[t][k].n_rows = r.n_rows;
+        a.src[t][k].capacity = r.capacity;
+    }
     return TENSAIR_OK;
 }
 
@@ -756,28 +775,14 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     return TENSAIR_OK;
 }
 
-static int fill_apply_src(ApplyArgs &a, int k, const tensair_sparse_grad *g, const char *what)
-{
-    const tensair_sparse_rows *side[2] = {&g->in, &g->out};
-    for (int t = 0; t < 2; ++t) {
-        const tensair_sparse_rows &r = *side[t];
-        if (!r.n_rows || !r.row_ids || !r.row_grads) return fail(TENSAIR_EINVAL, "%s: NULL pointer", what);
-        if (r.capacity < 0 || r.capacity > 0x7FFFFFFFLL) return fail(TENSAIR_EINVAL, "%s: bad capacity", what);
-        a.src[t][k].ids = r.row_ids;
-        a.src[t][k].rows = r.row_grads;
-        a.src[t][k].n_rows = r.n_rows;
-        a.src[t][k].capacity = r.capacity;
-    }
-    return TENSAIR_OK;
-}
-
+// peers are fp32 gradients (`peers`) or bfloat16 messages (`packed`), never both
 static int make_apply_args(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
-                           int32_t n_peers, float lr, ApplyArgs &a)
+                           const tensair_packed_grad *packed, int32_t n_peers, float lr, ApplyArgs &a)
 {
     const tensair_config &c = m->cfg;
     if (n_peers < 0 || n_peers > c.max_peers)
         return fail(TENSAIR_ECAPACITY, "n_peers %d outside 0..max_peers %d", n_peers, c.max_peers);
-    if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
+    if (n_peers > 0 && !peers && !packed) return fail(TENSAIR_EINVAL, "peers is NULL");
     if (!(lr == lr)) return fail(TENSAIR_EINVAL, "lr is NaN");
     memset(&a, 0, sizeof(a));
     a.table[0] = m->w_in;
@@ -789,6 +794,7 @@ static int make_apply_args(tensair_model *m, const tensair_sparse_grad *own, con
     a.n_src = 1 + n_peers;
     a.lr = lr;
     a.status = m->status;
+    a.packed = (packed != nullptr && n_peers > 0) ? 1 : 0;
     for (int t = 0; t < 2; ++t) {
         a.start[t] = m->start[t];
         a.mask[t] = m->mask[t];
@@ -796,16 +802,17 @@ static int make_apply_args(tensair_model *m, const tensair_sparse_grad *own, con
     int rc;
     if (own && (rc = fill_apply_src(a, 0, own, "own"))) return rc;
     for (int k = 0; k < n_peers; ++k)
-        if ((rc = fill_apply_src(a, 1 + k, &peers[k], "peer"))) return rc;
+        if ((rc = packed ? fill_apply_src(a, 1 + k, &packed[k], "peer") : fill_apply_src(a, 1 + k, &peers[k], "peer")))
+            return rc;
     return TENSAIR_OK;
 }
 
-int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
-                        int32_t n_peers, float lr, void *stream)
+static int apply_impl(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
+                      const tensair_packed_grad *packed, int32_t n_peers, float lr, void *stream)
 {
     if (!m) return fail(TENSAIR_EINVAL, "model is NULL");
     ApplyArgs a;
-    int rc = make_apply_args(m, own, peers, n_peers, lr, a);
+    int rc = make_apply_args(m, own, peers, packed, n_peers, lr, a);
     if (rc) return rc;
     if (!own && n_peers == 0) return TENSAIR_OK;
     hipStream_t st = (hipStream_t)stream;
@@ -815,6 +822,56 @@ int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const 
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
     mark(m, PF_APPLY_UPDATE, st);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_dasgd_apply(tensair_model *m, const tensair_sparse_grad *own, const tensair_sparse_grad *peers,
+                        int32_t n_peers, float lr, void *stream)
+{
+    return apply_impl(m, own, peers, nullptr, n_peers, lr, stream);
+}
+
+int tensair_dasgd_apply_packed(tensair_model *m, const tensair_sparse_grad *own, const tensair_packed_grad *peers,
+                               int32_t n_peers, float lr, void *stream)
+{
+    if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
+    return apply_impl(m, own, nullptr, peers, n_peers, lr, stream);
+}
+
+int tensair_grad_pack(tensair_model *m, const tensair_sparse_grad *g, tensair_packed_grad *out, void *stream)
+{
+    if (!m || !g || !out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
+    GradPackArgs a;
+    memset(&a, 0, sizeof(a));
+    a.D = m->cfg.dim;
+    a.status = m->status;
+    const tensair_sparse_rows *src[2] = {&g->in, &g->out};
+    const tensair_packed_rows *dst[2] = {&out->in, &out->out};
+    for (int t = 0; t < 2; ++t) {
+        const tensair_sparse_rows &r = *src[t];
+        const tensair_packed_rows &d = *dst[t];
+        if (!r.n_rows || !r.row_ids || !r.row_grads || !d.n_rows || !d.row_ids || !d.row_grads)
+            return fail(TENSAIR_EINVAL, "grad_pack: NULL pointer");
+        if (r.capacity < 0 || r.capacity > 0x7FFFFFFFLL || d.capacity < 0 || d.capacity > 0x7FFFFFFFLL)
+            return fail(TENSAIR_EINVAL, "grad_pack: bad capacity");
+        if (((uintptr_t)r.row_grads | (uintptr_t)d.row_grads) & 15)
+            return fail(TENSAIR_EINVAL, "grad_pack: rows must be 16-byte aligned");
+        if ((const void *)d.row_grads == (const void *)r.row_grads || d.row_ids == r.row_ids || d.n_rows == r.n_rows)
+            return fail(TENSAIR_EINVAL, "grad_pack: out must not share buffers with g");
+        a.n[t] = r.n_rows;
+        a.ids[t] = r.row_ids;
+        a.rows[t] = r.row_grads;
+        a.cap[t] = r.capacity;
+        a.out_n[t] = d.n_rows;
+        a.out_ids[t] = d.row_ids;
+        a.out_rows[t] = d.row_grads;
+        a.out_cap[t] = d.capacity;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    mark(m, PF_BEGIN_PACK, st);
+    tn_launch_grad_pack(a, st);
+    mark(m, PF_PACK, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }
@@ -864,14 +921,15 @@ int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensa
     return TENSAIR_OK;
 }
 
-int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
-                 int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers, int32_t n_peers,
-                 float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
+static int step_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                     int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers,
+                     const tensair_packed_grad *packed, int32_t n_peers, float lr, tensair_sparse_grad *own_out,
+                     float *mean_loss, void *stream)
 {
     if (!m || !own_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     // validate the apply arguments before anything is enqueued
     ApplyArgs a;
-    int rc = make_apply_args(m, own_out, peers, n_peers, lr, a);
+    int rc = make_apply_args(m, own_out, peers, packed, n_peers, lr, a);
     if (rc) return rc;
     m->fused_apply = &a;
     m->fused_index_done = false;
@@ -880,7 +938,8 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
         const tensair_config &c = m->cfg;
         const double occ = 2.0 * c.window * (double)n_centers * (c.negatives + 1);
         const double rows = occ < (double)c.vocab ? occ : (double)c.vocab;
-        const double t_apply = (double)a.n_src * rows * c.dim * 4.0 / 5e12;
+        const double src_bytes = 4.0 + (a.packed ? 2.0 : 4.0) * (a.n_src - 1);
+        const double t_apply = src_bytes * rows * c.dim / 5e12;
         const double t_prepare = occ * 0.2e-9 + 60e-6;
         m->prepare_under_apply = t_apply >= 2.0 * t_prepare;
     }
@@ -902,6 +961,23 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
     mark(m, PF_APPLY_UPDATE, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
+}
+
+int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                 int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers, int32_t n_peers,
+                 float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
+{
+    return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, peers, nullptr, n_peers, lr, own_out,
+                     mean_loss, stream);
+}
+
+int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                        int32_t n_centers, uint32_t epoch, const tensair_packed_grad *peers, int32_t n_peers,
+                        float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
+{
+    if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
+    return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, nullptr, peers, n_peers, lr, own_out,
+                     mean_loss, stream);
 }
 
 int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,
@@ -1020,8 +1096,8 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
     }
     for (size_t i = 1; i < m->prof_marks.size() && n < max_records; ++i) {
         const int tag = m->prof_marks[i].first;
-        if (tag == PF_BEGIN_GRAD || tag == PF_BEGIN_APPLY || tag == PF_BEGIN_ADD) continue;
-        if (m->prof_level == 1 && tag != PF_APPLY_UPDATE && tag != PF_ADD_ROWS) continue;
+        if (tag == PF_BEGIN_GRAD || tag == PF_BEGIN_APPLY || tag == PF_BEGIN_ADD || tag == PF_BEGIN_PACK) continue;
+        if (m->prof_level == 1 && tag != PF_APPLY_UPDATE && tag != PF_ADD_ROWS && tag != PF_PACK) continue;
         float t = 0.f;
         if (hipEventElapsedTime(&t, m->prof_marks[i - 1].second, m->prof_marks[i].second) != hipSuccess) continue;
         tags[n] = tag;

@@ -1,10 +1,13 @@
-// Three streaming operations around the worker step (TensAIR, arXiv 2211.10280):
+// Streaming operations around the worker step (TensAIR, arXiv 2211.10280):
 //   k_dense_apply   apply_gradient of Algorithm 1 / Eq. 1 for a dense model (Section 4, "Sparse vs.
 //                   Dense Models": every variable receives gradient): theta <- theta - alpha * sum_k g_k
 //                   for the own gradient and the gradients received from peers, one pass, one rounding
 //   k_lookup        predict of Algorithm 1 for an embedding model: the vectors of the given words
 //   k_cosine_diff   Section 4.4: 1 - cos between the embeddings of every word in two tables
-// All three are bound by HBM bandwidth: every byte is touched once, loads are 16 bytes per lane.
+//   k_grad_pack     a sparse gradient turned into a bfloat16 message (a variant beyond the paper, aimed
+//                   at what Section 4.3 names as the limit of Word2Vec scaling: gradient application
+//                   and the network)
+// All are bound by HBM bandwidth: every byte is touched once, loads are 16 bytes per lane.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -23,7 +26,8 @@ __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
     // through memory together (a grid-stride loop over a fixed grid was 12 % slower)
     const i64 c = (i64)blockIdx.x * BLOCK + threadIdx.x;
     if (c < n4) {
-        float4 w = STREAM ? ld4s(theta + 4 * c) : ld4(theta + 4 * c);
+        // theta stays as loaded (bf16 not yet widened) until the gradients' loads are out
+        const typename Raw4<T>::type wr = STREAM ? ldraw_s(theta + 4 * c) : ldraw(theta + 4 * c);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int k0 = 0; k0 < a.n_grads; k0 += DENSE_INFLIGHT) {
             float4 x[DENSE_INFLIGHT];
@@ -39,6 +43,7 @@ __global__ void __launch_bounds__(BLOCK) k_dense_apply(DenseApplyArgs a)
                 acc.w += x[j].w;
             }
         }
+        float4 w = widen4(wr);
         w.x = fmaf(neg_lr, acc.x, w.x);
         w.y = fmaf(neg_lr, acc.y, w.y);
         w.z = fmaf(neg_lr, acc.z, w.z);
@@ -131,9 +136,15 @@ __global__ void __launch_bounds__(BLOCK) k_cosine_diff(CosineArgs a)
     const int C4 = a.D >> 2;
     const i64 nw = (i64)gridDim.x * WAVES_PER_BLOCK;
     for (i64 r = (i64)blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6)); r < a.V; r += nw) {
+        typename Raw4<T>::type xr[ITERS], yr[ITERS];
+        load_row_raw<T, ITERS, 1>(xr, (const T *)a.a + (size_t)r * a.stride, C4, lane);   // read once
+        load_row_raw<T, ITERS, 1>(yr, (const T *)a.b + (size_t)r * a.stride, C4, lane);
         float4 x[ITERS], y[ITERS];
-        load_row_s<T, ITERS>(x, (const T *)a.a + (size_t)r * a.stride, C4, lane);   // read once
-        load_row_s<T, ITERS>(y, (const T *)a.b + (size_t)r * a.stride, C4, lane);
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            x[it] = widen4(xr[it]);
+            y[it] = widen4(yr[it]);
+        }
         const float dot = wave_sum_dpp(dot_partial<ITERS>(x, y));
         const float na = wave_sum_dpp(dot_partial<ITERS>(x, x));
         const float nb = wave_sum_dpp(dot_partial<ITERS>(y, y));
@@ -163,4 +174,47 @@ void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st)
     if (a.V <= 0) return;
     if (a.dtype == 0) launch_cosine_t<float>(a, st);
     else launch_cosine_t<bf16_t>(a, st);
+}
+
+// ---------------------------------------------------------------- gradient message in bfloat16
+// grid (blocks, 2 tables).  The rows of a sparse gradient are dense, [n][D], so the conversion is flat:
+// thread c rounds chunk c (4 elements, to nearest even) and, while c < n, copies row id c.  The launch
+// covers the capacity; workgroups beyond the n rows that are there leave at once.
+__global__ void __launch_bounds__(BLOCK) k_grad_pack(GradPackArgs a)
+{
+    const int tb = blockIdx.y;
+    i64 n = *a.n[tb];
+    if (n < 0) n = 0;
+    bool over = false;
+    if (n > a.cap[tb]) {   // the source claims more rows than it holds
+        n = a.cap[tb];
+        over = true;
+    }
+    if (n > a.out_cap[tb]) {
+        n = a.out_cap[tb];
+        over = true;
+    }
+    const i64 first = (i64)blockIdx.x * BLOCK + threadIdx.x;
+    const i64 step = (i64)gridDim.x * BLOCK;
+    if (first == 0) {
+        *a.out_n[tb] = (int)n;
+        if (over) atomicOr(a.status, ST_OVERFLOW);
+    }
+    const i64 chunks = n * (a.D >> 2);
+    for (i64 c = first; c < chunks; c += step) {   // one pass unless the gradient is larger than the largest grid
+        if (c < n) a.out_ids[tb][c] = a.ids[tb][c];
+        st4s(a.out_rows[tb] + 4 * c, ld4s(a.rows[tb] + 4 * c));
+    }
+}
+
+void tn_launch_grad_pack(const GradPackArgs &a, hipStream_t st)
+{
+    i64 chunks = 1;
+    for (int tb = 0; tb < 2; ++tb) {
+        const i64 rows = a.cap[tb] < a.out_cap[tb] ? a.cap[tb] : a.out_cap[tb];
+        if (rows * (a.D >> 2) > chunks) chunks = rows * (a.D >> 2);
+    }
+    i64 want = (chunks + BLOCK - 1) / BLOCK;
+    const int blocks = (int)(want > (1 << 22) ? (1 << 22) : want);
+    hipLaunchKernelGGL(k_grad_pack, dim3(blocks, 2), dim3(BLOCK), 0, st, a);
 }

@@ -75,6 +75,32 @@ __device__ __forceinline__ void st4s(bf16_t *p, float4 v)
     __builtin_nontemporal_store(r, (GLOBAL_AS v2u *)p);
 }
 
+// A 4-element chunk as it comes from memory: a float4 for fp32, two words (4 x bfloat16) for bf16.  Where
+// several rows are loaded at a time the chunks stay in this form until they are used: a conversion placed
+// next to its load makes the compiler wait for the data right there, one round trip per load instead of
+// one per batch.
+template <typename T> struct Raw4;
+template <> struct Raw4<float> { typedef float4 type; };
+template <> struct Raw4<bf16_t> { typedef uint2 type; };
+__device__ __forceinline__ float4 widen4(float4 v) { return v; }
+__device__ __forceinline__ float4 widen4(uint2 r)
+{
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ float widen1(float v) { return v; }
+__device__ __forceinline__ float widen1(bf16_t v) { return bf16_to_f32(v); }
+__device__ __forceinline__ void zero_raw(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void zero_raw(uint2 &v) { v = make_uint2(0u, 0u); }
+__device__ __forceinline__ float4 ldraw(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ uint2 ldraw(const bf16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
+__device__ __forceinline__ float4 ldraw_s(const float *p) { return ld4s(p); }
+__device__ __forceinline__ uint2 ldraw_s(const bf16_t *p)
+{
+    v2u r = __builtin_nontemporal_load((const GLOBAL_AS v2u *)p);
+    return make_uint2(r.x, r.y);
+}
+
 // A row of D = 4*C4 elements is held by one wave: lane l owns chunks l, l+64, ...
 // (ITERS = ceil(C4/64) chunks per lane, compile-time).
 template <typename T, int ITERS>
@@ -84,6 +110,49 @@ __device__ __forceinline__ void load_row(float4 (&r)[ITERS], const T *row, int C
     for (int it = 0; it < ITERS; ++it) {
         int c = lane + WAVE * it;
         r[it] = (c < C4) ? ld4(row + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+// the same, chunks left as loaded; MODE 0: through the caches, 1: around them (non-temporal), 2: around
+// them except for the (at most two) 128-byte lines that the row shares with its neighbours in memory,
+// so that the neighbour finds those in the cache
+template <typename T, int ITERS, int MODE>
+__device__ __forceinline__ void load_row_raw(typename Raw4<T>::type (&r)[ITERS], const T *row, int C4, int lane)
+{
+    const uintptr_t lo = (uintptr_t)row, hi = lo + (size_t)C4 * 4 * sizeof(T);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        int c = lane + WAVE * it;
+        zero_raw(r[it]);
+        if (c < C4) {
+            if (MODE == 0) {
+                r[it] = ldraw(row + 4 * c);
+            } else if (MODE == 1) {
+                r[it] = ldraw_s(row + 4 * c);
+            } else {
+                const uintptr_t line = (uintptr_t)(row + 4 * c) & ~(uintptr_t)127;
+                if (line >= lo && line + 128 <= hi) r[it] = ldraw_s(row + 4 * c);
+                else r[it] = ldraw(row + 4 * c);
+            }
+        }
+    }
+}
+template <int ITERS, typename R>
+__device__ __forceinline__ void zero_row_raw(R (&r)[ITERS])
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) zero_raw(r[it]);
+}
+// acc += x for a row of chunks as loaded
+template <int ITERS, typename R>
+__device__ __forceinline__ void add_row_raw(float4 (&acc)[ITERS], const R (&x)[ITERS])
+{
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const float4 v = widen4(x[it]);
+        acc[it].x += v.x;
+        acc[it].y += v.y;
+        acc[it].z += v.z;
+        acc[it].w += v.w;
     }
 }
 template <typename T, int ITERS>
@@ -111,24 +180,6 @@ __device__ __forceinline__ void store_row_s(T *row, const float4 (&r)[ITERS], in
     for (int it = 0; it < ITERS; ++it) {
         int c = lane + WAVE * it;
         if (c < C4) st4s(row + 4 * c, r[it]);
-    }
-}
-// Streaming load of a whole row whose ends need not fall on cache-line borders: the 128-byte lines
-// that the row fills completely go around the caches, the (at most two) lines it shares with its
-// neighbours in memory go through them, so that the neighbour finds them there.
-template <typename T, int ITERS>
-__device__ __forceinline__ void load_row_edges(float4 (&r)[ITERS], const T *row, int C4, int lane)
-{
-    const uintptr_t lo = (uintptr_t)row, hi = lo + (size_t)C4 * 4 * sizeof(T);
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        int c = lane + WAVE * it;
-        r[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c < C4) {
-            const uintptr_t line = (uintptr_t)(row + 4 * c) & ~(uintptr_t)127;
-            if (line >= lo && line + 128 <= hi) r[it] = ld4s(row + 4 * c);
-            else r[it] = ld4(row + 4 * c);
-        }
     }
 }
 template <int ITERS>

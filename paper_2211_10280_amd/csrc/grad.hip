@@ -27,24 +27,53 @@
 // most 64 of them).  The second form is for dimensions just above a multiple of 256 -- D = 300 is
 // 256 + 44 -- where a float4 that only 11 lanes use would cost every lane four registers per row; with
 // one float instead, twice as many rows fit in flight at the same occupancy.
-template <int NQ, bool TAIL>
-struct WaveRow {
-    float4 q[NQ];
-    float t;
+// LoadedRow is such a row as it comes from memory (a bf16 row not yet widened), WaveRow one in fp32 that
+// arithmetic is done on.  Rows that are loaded several at a time are kept as LoadedRow until they are
+// used, so that all loads of a batch are issued before the first wait.
+template <typename T, int NQ, bool TAIL>
+struct LoadedRow {
+    typename Raw4<T>::type q[NQ];
+    T t;
 
-    template <typename T>
     __device__ __forceinline__ void load(const T *row, int D, int lane)
     {
         const int C4 = TAIL ? NQ * WAVE : (D >> 2);
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
             const int c = lane + WAVE * it;
-            q[it] = (c < C4) ? ld4(row + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+            zero_raw(q[it]);
+            if (c < C4) q[it] = ldraw(row + 4 * c);
         }
         if (TAIL) {
             const int e = 4 * WAVE * NQ + lane;
-            t = (e < D) ? elem(row, e) : 0.f;
+            t = (e < D) ? row[e] : (T)0;
         }
+    }
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) zero_raw(q[it]);
+        t = (T)0;
+    }
+    __device__ __forceinline__ float4 chunk(int it) const { return widen4(q[it]); }
+    __device__ __forceinline__ float tail() const { return widen1(t); }
+};
+
+template <int NQ, bool TAIL>
+struct WaveRow {
+    float4 q[NQ];
+    float t;
+
+    __device__ __forceinline__ float4 chunk(int it) const { return q[it]; }
+    __device__ __forceinline__ float tail() const { return t; }
+    template <typename T>
+    __device__ __forceinline__ void load(const T *row, int D, int lane)
+    {
+        LoadedRow<T, NQ, TAIL> r;
+        r.load(row, D, lane);
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) q[it] = r.chunk(it);
+        t = TAIL ? r.tail() : 0.f;
     }
     __device__ __forceinline__ void zero()
     {
@@ -52,29 +81,33 @@ struct WaveRow {
         for (int it = 0; it < NQ; ++it) q[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         t = 0.f;
     }
-    __device__ __forceinline__ float dot(const WaveRow &o) const
+    template <typename R>
+    __device__ __forceinline__ float dot(const R &o) const
     {
         float s = 0.f;
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
-            s = fmaf(q[it].x, o.q[it].x, s);
-            s = fmaf(q[it].y, o.q[it].y, s);
-            s = fmaf(q[it].z, o.q[it].z, s);
-            s = fmaf(q[it].w, o.q[it].w, s);
+            const float4 v = o.chunk(it);
+            s = fmaf(q[it].x, v.x, s);
+            s = fmaf(q[it].y, v.y, s);
+            s = fmaf(q[it].z, v.z, s);
+            s = fmaf(q[it].w, v.w, s);
         }
-        if (TAIL) s = fmaf(t, o.t, s);
+        if (TAIL) s = fmaf(t, o.tail(), s);
         return s;
     }
-    __device__ __forceinline__ void axpy(float a, const WaveRow &x)
+    template <typename R>
+    __device__ __forceinline__ void axpy(float a, const R &x)
     {
 #pragma unroll
         for (int it = 0; it < NQ; ++it) {
-            q[it].x = fmaf(a, x.q[it].x, q[it].x);
-            q[it].y = fmaf(a, x.q[it].y, q[it].y);
-            q[it].z = fmaf(a, x.q[it].z, q[it].z);
-            q[it].w = fmaf(a, x.q[it].w, q[it].w);
+            const float4 v = x.chunk(it);
+            q[it].x = fmaf(a, v.x, q[it].x);
+            q[it].y = fmaf(a, v.y, q[it].y);
+            q[it].z = fmaf(a, v.z, q[it].z);
+            q[it].w = fmaf(a, v.w, q[it].w);
         }
-        if (TAIL) t = fmaf(a, x.t, t);
+        if (TAIL) t = fmaf(a, x.tail(), t);
     }
     // element e of the row goes to dst[e]; dst has room for every lane's registers
     __device__ __forceinline__ void spill(float *dst, int lane) const
@@ -110,8 +143,6 @@ struct WaveRow {
             }
         }
     }
-    static __device__ __forceinline__ float elem(const float *row, int e) { return row[e]; }
-    static __device__ __forceinline__ float elem(const bf16_t *row, int e) { return bf16_to_f32(row[e]); }
 };
 
 // rows in flight per wave: as many as fit in 64 registers per lane (8 waves per SIMD).  Measured: with
@@ -119,16 +150,16 @@ struct WaveRow {
 // million words the pass moves 0.46 GB of rows through the fabric at the rate random 1.2 KB gathers
 // get (5.7 TB/s) and neither more rows in flight, nor prefetching the row ids, nor software pipelining,
 // nor keeping neighbouring centers on one XCD changes its time.
-template <int NQ, bool TAIL>
+template <typename T, int NQ, bool TAIL>
 struct FwdShape {
-    static constexpr int regs = 4 * NQ + (TAIL ? 1 : 0);
+    static constexpr int regs = (sizeof(T) == 2 ? 2 : 4) * NQ + (TAIL ? 1 : 0);   // of a row as loaded
     static constexpr int unroll = regs <= 5 ? 4 : 2;
 };
 
 // rows in flight per wave in the segmented reduction
-template <int NQ, bool TAIL>
+template <typename T, int NQ, bool TAIL>
 struct SegShape {
-    static constexpr int regs = 4 * NQ + (TAIL ? 1 : 0);
+    static constexpr int regs = (sizeof(T) == 2 ? 2 : 4) * NQ + (TAIL ? 1 : 0);
     static constexpr int unroll = regs <= 5 ? 2 * SEG_UNROLL : SEG_UNROLL;
 };
 
@@ -137,7 +168,7 @@ template <typename T, int NQ, bool TAIL, bool LOSS>
 __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
 {
     typedef WaveRow<NQ, TAIL> Row;
-    constexpr int UNROLL = FwdShape<NQ, TAIL>::unroll;
+    constexpr int UNROLL = FwdShape<T, NQ, TAIL>::unroll;
     __shared__ float red[WAVES_PER_BLOCK][(NQ * 4 + (TAIL ? 1 : 0)) * WAVE];
     __shared__ float lred[WAVES_PER_BLOCK];
     const int i = blockIdx.x;
@@ -164,7 +195,7 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
     // dot products are reduced one by one, then lane x evaluates the sigmoid of task x, so the
     // transcendental code runs once per group instead of once per task.
     for (int t0 = wave; t0 < ntasks; t0 += WAVES_PER_BLOCK * UNROLL) {
-        Row u[UNROLL];
+        LoadedRow<T, NQ, TAIL> u[UNROLL];
 #pragma unroll
         for (int x = 0; x < UNROLL; ++x) {
             int t = t0 + x * WAVES_PER_BLOCK;
@@ -276,7 +307,7 @@ template <typename T, int NQ, bool TAIL, int MODE, int TILE>
 __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block)
 {
     typedef WaveRow<NQ, TAIL> Row;
-    constexpr int UNROLL = SegShape<NQ, TAIL>::unroll;
+    constexpr int UNROLL = SegShape<T, NQ, TAIL>::unroll;
     static_assert(2 * TILE <= WAVE, "a wave keeps the metadata of two tiles in its lanes");
     // the wave index is made explicitly wave-uniform so that all the control flow below is scalar
     const int tile = block * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6));
@@ -355,7 +386,7 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
     };
 
     for (int e0 = e_begin; e0 < e_end; e0 += UNROLL) {
-        Row r[UNROLL];
+        LoadedRow<T, NQ, TAIL> r[UNROLL];
         float sc[UNROLL];
         int sg[UNROLL];
 #pragma unroll

@@ -126,7 +126,7 @@ void tn_launch_empty_grad(int *n_in, int *n_out, float *mean_loss, int *seg_in, 
 // ---- stage 6/7: DASGD merge and table update
 struct ApplySrc {
     const int *ids;
-    const float *rows;
+    const void *rows;        // [capacity][D] fp32; bfloat16 for the sources 1.. of a call with packed peers
     const int *n_rows;
     i64 capacity;
 };
@@ -140,6 +140,7 @@ struct ApplyArgs {
     u64 *mask[2];            // [words][n_src]
     float lr;
     int *status;
+    int packed;              // 1: the peers' rows (sources 1..) are bfloat16 messages, the own gradient's fp32
 };
 void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st);
 void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st);
@@ -158,6 +159,18 @@ struct GradSumArgs {
 #define TN_UNION_WORDS 1024  // vocabulary words per workgroup in the union scan (256 threads x 4)
 void tn_launch_grad_sum_index(const GradSumArgs &g, hipStream_t st);   // index + scan
 void tn_launch_grad_sum_rows(const GradSumArgs &g, hipStream_t st);    // the rows themselves
+
+// ---- a sparse gradient as a bfloat16 message: row counts and ids copied, rows rounded to nearest even
+struct GradPackArgs {
+    const int *n[2], *ids[2];
+    const float *rows[2];
+    int *out_n[2], *out_ids[2];
+    unsigned short *out_rows[2];
+    i64 cap[2], out_cap[2];
+    int D;
+    int *status;
+};
+void tn_launch_grad_pack(const GradPackArgs &a, hipStream_t st);
 
 // ---- dense-model apply, embedding lookup, cosine difference between two tables
 struct DenseApplyArgs {

@@ -10,6 +10,8 @@ steps old (the staleness of Section 3.1, counted in this worker's steps).
 With maxGradBuffer = n > 1 (Algorithm 1) every instance sums its gradients with
 ``tensair_grad_add`` and sends the sum after every n-th step, so the K peer
 buffers arrive together at steps n-1, 2n-1, ... and none in between.
+With ``bf16_messages`` the peers' gradients travel as bfloat16 messages
+(``tensair_grad_pack`` on the sender's side, ``tensair_step_packed`` here).
 Everything numerical happens inside the library; this file only sequences calls
 and keeps buffers.
 """
@@ -24,8 +26,9 @@ from . import workload as W
 
 class DasgdWorker:
     def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True,
-                 row_stride=None):
+                 row_stride=None, bf16_messages=False):
         self.cfg = cfg
+        self.bf16_messages = bf16_messages
         self.prefetch = prefetch     # announce coming mini-batches with tensair_prefetch
         self.announced = -1          # last step whose mini-batch has been announced
         self.device = device
@@ -54,6 +57,10 @@ class DasgdWorker:
                                         cfg.dim, device)
             self.own_acc = [big(), big()]
             self.peer_acc = [[big(), big()] for _ in range(cfg.peers)]
+        if bf16_messages:
+            n = max(cfg.grad_buffer, 1)
+            self.peer_msgs = [B.PackedBuffers(min(cfg.vocab, n * self.own.cap_in), min(cfg.vocab, n * self.own.cap_out),
+                                              cfg.dim, device) for _ in range(cfg.peers)]
 
     # -- peers -------------------------------------------------------------
     def _snapshot(self, t):
@@ -78,9 +85,12 @@ class DasgdWorker:
             begin, n, epoch = W.worker_batch(cfg, t, k)
             self.peer_model.rebind(w_in, w_out, k)
             self.peer_model.sgns_grad(self.tokens, begin, n, epoch, self.peer_bufs[k - 1])
-        if cfg.grad_buffer > 1:
-            return self._buffer_peers(t)
-        return self.peer_bufs
+        out = self._buffer_peers(t) if cfg.grad_buffer > 1 else self.peer_bufs
+        if self.bf16_messages:     # what a peer sends is rounded once, after any summing in its buffer
+            for g, msg in zip(out, self.peer_msgs):
+                self.model.grad_pack(g, msg)
+            out = self.peer_msgs[:len(out)]
+        return out
 
     def _accumulate(self, pair, g, first):
         """pair[0] <- pair[0] + g (gradients += gradient); an empty sum at the start of a window."""
@@ -108,8 +118,9 @@ class DasgdWorker:
         # prepares it during the step
         if self.prefetch and self.announced == t:
             self._announce(t + 1)
-        self.model.step(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
-                        self.mean_loss if want_loss else None)
+        packed = len(peers) > 0 and isinstance(peers[0], B.PackedBuffers)
+        (self.model.step_packed if packed else self.model.step)(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
+                                                                self.mean_loss if want_loss else None)
         if cfg.grad_buffer > 1:
             self._accumulate(self.own_acc, self.own, t % cfg.grad_buffer == 0)
             if (t + 1) % cfg.grad_buffer == 0:

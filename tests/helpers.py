@@ -16,6 +16,15 @@ BF16_ULP = 2
 # and the maximum; single applications from identical inputs are held to 2 ulp outright.
 BF16_CHAIN_FRAC = 1e-6
 BF16_CHAIN_MAX = 4
+# the same chains with the peers' gradients sent as bfloat16 messages: a message element is a rounding
+# decision taken from gradients that differ between the two sides by their own error (up to 1e-4 of a
+# row, more once bf16 tables have drifted apart by a rounding), so an element within that distance of a
+# rounding boundary -- a fraction of about error / 2^-8 -- comes out one bfloat16 step apart on the two
+# sides.  One such step is 2^-8 of that peer's gradient element, which, against a table element that is
+# itself a sum of a few such gradients times alpha, is of the order of one table ulp per flipped message,
+# and more where the gradients cancel.  (From identical messages the application is held to 2 ulp.)
+BF16_MSG_CHAIN_FRAC = 1e-4
+BF16_MSG_CHAIN_MAX = 16
 
 
 def rel_l2(a, b):
