@@ -177,9 +177,12 @@ void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st)
 }
 
 // ---------------------------------------------------------------- gradient message in bfloat16
-// grid (blocks, 2 tables).  The rows of a sparse gradient are dense, [n][D], so the conversion is flat:
-// thread c rounds chunk c (4 elements, to nearest even) and, while c < n, copies row id c.  The launch
-// covers the capacity; workgroups beyond the n rows that are there leave at once.
+// grid (blocks, 2 tables).  The rows of a sparse gradient are dense, [n][D], so the conversion is flat: a
+// workgroup rounds PACK_CHUNKS * 256 consecutive chunks of 4 elements (to nearest even), a thread one
+// chunk of every 256, all its loads issued before the first store; the row ids are copied by the threads
+// whose chunk index is below n.  The launch covers the capacity (n is only known on the device);
+// workgroups beyond the n rows that are there leave at once.
+#define PACK_CHUNKS 4
 __global__ void __launch_bounds__(BLOCK) k_grad_pack(GradPackArgs a)
 {
     const int tb = blockIdx.y;
@@ -194,16 +197,26 @@ __global__ void __launch_bounds__(BLOCK) k_grad_pack(GradPackArgs a)
         n = a.out_cap[tb];
         over = true;
     }
-    const i64 first = (i64)blockIdx.x * BLOCK + threadIdx.x;
-    const i64 step = (i64)gridDim.x * BLOCK;
-    if (first == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         *a.out_n[tb] = (int)n;
         if (over) atomicOr(a.status, ST_OVERFLOW);
     }
     const i64 chunks = n * (a.D >> 2);
-    for (i64 c = first; c < chunks; c += step) {   // one pass unless the gradient is larger than the largest grid
-        if (c < n) a.out_ids[tb][c] = a.ids[tb][c];
-        st4s(a.out_rows[tb] + 4 * c, ld4s(a.rows[tb] + 4 * c));
+    const i64 step = (i64)gridDim.x * BLOCK * PACK_CHUNKS;
+    // one pass unless the gradient is larger than the largest grid
+    for (i64 base = (i64)blockIdx.x * BLOCK * PACK_CHUNKS + threadIdx.x; base < chunks; base += step) {
+        float4 v[PACK_CHUNKS];
+#pragma unroll
+        for (int j = 0; j < PACK_CHUNKS; ++j) {
+            const i64 c = base + (i64)j * BLOCK;
+            v[j] = (c < chunks) ? ld4s(a.rows[tb] + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < PACK_CHUNKS; ++j) {
+            const i64 c = base + (i64)j * BLOCK;
+            if (c < n) a.out_ids[tb][c] = a.ids[tb][c];
+            if (c < chunks) st4s(a.out_rows[tb] + 4 * c, v[j]);
+        }
     }
 }
 
@@ -214,7 +227,7 @@ void tn_launch_grad_pack(const GradPackArgs &a, hipStream_t st)
         const i64 rows = a.cap[tb] < a.out_cap[tb] ? a.cap[tb] : a.out_cap[tb];
         if (rows * (a.D >> 2) > chunks) chunks = rows * (a.D >> 2);
     }
-    i64 want = (chunks + BLOCK - 1) / BLOCK;
+    i64 want = (chunks + BLOCK * PACK_CHUNKS - 1) / (BLOCK * PACK_CHUNKS);
     const int blocks = (int)(want > (1 << 22) ? (1 << 22) : want);
     hipLaunchKernelGGL(k_grad_pack, dim3(blocks, 2), dim3(BLOCK), 0, st, a);
 }
