@@ -68,7 +68,15 @@ typedef struct {
     int32_t max_peers;   /* largest number of peer gradients a call may pass, <= TENSAIR_MAX_PEERS */
     uint32_t worker_id;  /* < 65536; enters the negative-sampling counter (peers differ by it) */
     uint64_t seed;       /* key of the counter-based generator (negatives and table init) */
+    uint32_t flags;      /* 0, or TENSAIR_RESAMPLE_NEGATIVES */
 } tensair_config;
+
+/* A variant the paper leaves open (it does not say what happens to a negative that equals the pair's
+ * center or context word; by default it is kept and the row receives both contributions): with this
+ * flag such a negative is drawn once more, from words 2 and 3 of the same Philox block (bucket by
+ * multiply-high of word 2, word 3 against the threshold), and the second draw is kept whatever it
+ * is.  Still a pure function of the counter, with fixed shapes. */
+#define TENSAIR_RESAMPLE_NEGATIVES 1u
 
 /* One table's sparse gradient: the rows a mini-batch touches (Section 4, "Sparse vs.
  * Dense Models").  All pointers DEVICE, caller-owned.  row_ids[0..*n_rows) is strictly

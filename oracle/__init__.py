@@ -51,6 +51,8 @@ def lib():
         L.orc_pairs.restype = i64
         L.orc_sample_negatives.argtypes = [i64, vp, vp, u64, u32, u32, i64, vp, vp, i32, vp]
         L.orc_sample_negatives.restype = None
+        L.orc_sample_negatives_resampled.argtypes = [i64, vp, vp, u64, u32, u32, i64, vp, vp, i32, vp, i32, vp]
+        L.orc_sample_negatives_resampled.restype = None
         L.orc_init_tables.argtypes = [i64, i32, i32, C.c_int, u64, vp, vp]
         L.orc_init_tables.restype = None
         L.orc_sgns_grad.argtypes = [vp, i64, i32, i32, i64, i32, i64, i32, i32, C.c_int,
@@ -104,12 +106,20 @@ def pairs(T, w, begin, n):
     return pos[:P], q[:P]
 
 
-def sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N):
+def sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N, resample_tok=None, w=None):
+    """The N negatives of every pair (pos, q).  With ``resample_tok`` (the token stream) and the window
+    ``w``: the variant in which a negative equal to the pair's center or context word is drawn once
+    more, from the other two words of the same Philox block."""
     pos = np.ascontiguousarray(pos, dtype=np.int64)
     q = np.ascontiguousarray(q, dtype=np.int32)
     P = pos.shape[0]
     out = np.zeros((P, N), dtype=np.int32)
-    lib().orc_sample_negatives(V, _p(thr), _p(alias), seed, worker, epoch, P, _p(pos), _p(q), N, _p(out))
+    if resample_tok is None:
+        lib().orc_sample_negatives(V, _p(thr), _p(alias), seed, worker, epoch, P, _p(pos), _p(q), N, _p(out))
+    else:
+        tok = np.ascontiguousarray(resample_tok, dtype=np.int32)
+        lib().orc_sample_negatives_resampled(V, _p(thr), _p(alias), seed, worker, epoch, P, _p(pos), _p(q), N,
+                                             _p(tok), w, _p(out))
     return out
 
 
@@ -147,11 +157,15 @@ class Grad:
 
 
 def sgns_grad(tok, w, N, begin, n_centers, D, dtype, W_in, W_out, thr, alias,
-              seed, worker, epoch, neg_override=None, want64=False) -> Grad:
-    """calculate_gradient of Algorithm 1 for one mini-batch of centers."""
+              seed, worker, epoch, neg_override=None, want64=False, resample=False) -> Grad:
+    """calculate_gradient of Algorithm 1 for one mini-batch of centers.  ``resample``: the variant
+    of ``sample_negatives`` that draws colliding negatives once more."""
     tok = np.ascontiguousarray(tok, dtype=np.int32)
     T = tok.shape[0]
     V, stride = W_in.shape
+    if resample and neg_override is None:
+        pos, q = pairs(T, w, begin, n_centers)
+        neg_override = sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N, resample_tok=tok, w=w)
     assert W_in.dtype == _NP[dtype] and W_out.dtype == _NP[dtype]
     assert W_in.flags.c_contiguous and W_out.flags.c_contiguous
     if neg_override is not None:

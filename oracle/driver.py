@@ -48,7 +48,7 @@ class OracleWorker:
     def _grad(self, W_in, W_out, begin, n, epoch, worker):
         c = self.cfg
         return oracle.sgns_grad(self.tok, c.window, c.negatives, begin, n, c.dim, self.dtype, W_in, W_out,
-                                self.thr, self.alias, c.seed, worker, epoch)
+                                self.thr, self.alias, c.seed, worker, epoch, resample=c.resample)
 
     def step(self, n_steps_hint=4096):
         c = self.cfg

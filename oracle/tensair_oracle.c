@@ -105,11 +105,10 @@ int orc_alias_build(const uint64_t *counts, int64_t V, uint32_t *thr, int32_t *a
 /* One negative: counter = (position low, position high, q*65536 + slot,
  * worker + 65536*epoch), key = seed.  Word 0 picks the bucket by
  * multiply-high, word 1 is compared with the threshold.                */
-static int32_t draw_negative(int64_t V, const uint32_t *thr, const int32_t *alias,
-                             uint64_t seed, uint32_t worker, uint32_t epoch,
-                             int64_t pos, int32_t q, int32_t slot)
+static void negative_words(uint64_t seed, uint32_t worker, uint32_t epoch,
+                           int64_t pos, int32_t q, int32_t slot, uint32_t r[4])
 {
-    uint32_t ctr[4], key[2], r[4];
+    uint32_t ctr[4], key[2];
     ctr[0] = (uint32_t)((uint64_t)pos & 0xFFFFFFFFu);
     ctr[1] = (uint32_t)((uint64_t)pos >> 32);
     ctr[2] = (uint32_t)q * 65536u + (uint32_t)slot;
@@ -117,8 +116,21 @@ static int32_t draw_negative(int64_t V, const uint32_t *thr, const int32_t *alia
     key[0] = (uint32_t)(seed & 0xFFFFFFFFu);
     key[1] = (uint32_t)(seed >> 32);
     orc_philox4x32_10(ctr, key, r);
-    int64_t b = (int64_t)(((uint64_t)r[0] * (uint64_t)V) >> 32);
-    return (r[1] < thr[b]) ? (int32_t)b : alias[b];
+}
+
+static int32_t alias_pick(int64_t V, const uint32_t *thr, const int32_t *alias, uint32_t r_bucket, uint32_t r_accept)
+{
+    int64_t b = (int64_t)(((uint64_t)r_bucket * (uint64_t)V) >> 32);
+    return (r_accept < thr[b]) ? (int32_t)b : alias[b];
+}
+
+static int32_t draw_negative(int64_t V, const uint32_t *thr, const int32_t *alias,
+                             uint64_t seed, uint32_t worker, uint32_t epoch,
+                             int64_t pos, int32_t q, int32_t slot)
+{
+    uint32_t r[4];
+    negative_words(seed, worker, epoch, pos, q, slot, r);
+    return alias_pick(V, thr, alias, r[0], r[1]);
 }
 
 /* ------------------------------------------------------------------ */
@@ -149,6 +161,30 @@ void orc_sample_negatives(int64_t V, const uint32_t *thr, const int32_t *alias,
     for (int64_t i = 0; i < P; ++i)
         for (int32_t k = 0; k < N; ++k)
             neg_out[i * N + k] = draw_negative(V, thr, alias, seed, worker, epoch, pos[i], q[i], k);
+}
+
+/* A variant the paper leaves open (it does not say what happens when a negative
+ * equals the pair's center or context word; the base reading keeps it): such a
+ * negative is drawn again, once, from words 2 and 3 of the same Philox block, and
+ * the second draw is kept whatever it is -- still a pure function of the counter,
+ * with fixed shapes.  tok: the token stream; the pair (pos, q) has center tok[pos]
+ * and context tok[pos + offset(q)].                                              */
+void orc_sample_negatives_resampled(int64_t V, const uint32_t *thr, const int32_t *alias,
+                                    uint64_t seed, uint32_t worker, uint32_t epoch,
+                                    int64_t P, const int64_t *pos, const int32_t *q,
+                                    int32_t N, const int32_t *tok, int32_t w, int32_t *neg_out)
+{
+    for (int64_t i = 0; i < P; ++i) {
+        int64_t o = (q[i] < w) ? (int64_t)q[i] - w : (int64_t)q[i] - w + 1;
+        int32_t center = tok[pos[i]], context = tok[pos[i] + o];
+        for (int32_t k = 0; k < N; ++k) {
+            uint32_t r[4];
+            negative_words(seed, worker, epoch, pos[i], q[i], k, r);
+            int32_t id = alias_pick(V, thr, alias, r[0], r[1]);
+            if (id == center || id == context) id = alias_pick(V, thr, alias, r[2], r[3]);
+            neg_out[i * N + k] = id;
+        }
+    }
 }
 
 /* ------------------------------------------------------------------ */

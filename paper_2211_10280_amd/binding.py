@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtensair.so")
 F32, BF16 = 0, 1
 OK, EINVAL, ECAPACITY, EHIP, EDATA = 0, -1, -2, -3, -4
 MAX_PEERS = 31
+RESAMPLE_NEGATIVES = 1
 
 SYMBOLS = [
     "tensair_workspace_bytes", "tensair_capacity_in", "tensair_capacity_out", "tensair_model_init",
@@ -43,7 +44,7 @@ class Config(C.Structure):
     _fields_ = [("vocab", C.c_int64), ("dim", C.c_int32), ("row_stride", C.c_int32),
                 ("dtype", C.c_int32), ("window", C.c_int32), ("negatives", C.c_int32),
                 ("max_centers", C.c_int32), ("max_peers", C.c_int32), ("worker_id", C.c_uint32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("flags", C.c_uint32)]
 
 
 class SparseRows(C.Structure):
@@ -353,9 +354,9 @@ class Model:
     C entry points.  No arithmetic happens here."""
 
     def __init__(self, vocab, dim, dtype, window, negatives, max_centers, max_peers, seed,
-                 unigram_counts, worker_id=0, row_stride=None, tables=None, device="cuda"):
+                 unigram_counts, worker_id=0, row_stride=None, tables=None, device="cuda", flags=0):
         self.cfg = Config(vocab, dim, row_stride or dim, dtype, window, negatives, max_centers,
-                          max_peers, worker_id, seed)
+                          max_peers, worker_id, seed, flags)
         tdt = torch.float32 if dtype == F32 else torch.bfloat16
         if tables is None:
             self.w_in = torch.empty((vocab, self.cfg.row_stride), dtype=tdt, device=device)

@@ -58,6 +58,7 @@ bool config_ok(const tensair_config *c, const char **why)
     if (c->max_centers < 1) { *why = "max_centers must be positive"; return false; }
     if (c->max_peers < 0 || c->max_peers > TENSAIR_MAX_PEERS) { *why = "max_peers out of range"; return false; }
     if (c->worker_id >= 65536u) { *why = "worker_id must be below 65536"; return false; }
+    if (c->flags & ~TENSAIR_RESAMPLE_NEGATIVES) { *why = "unknown flag"; return false; }
     i64 omax = (i64)2 * c->window * c->max_centers * (c->negatives + 1);
     if (omax + c->max_centers >= 0x7FFFFFFFLL) { *why = "batch too large: occurrences must fit 31 bits"; return false; }
     return true;
@@ -460,8 +461,9 @@ static BatchWork batch_work(const tensair_config &c, const int32_t *tokens, i64 
 static void enqueue_keys(tensair_model *m, BatchSet &S, const BatchWork &w, int32_t *negatives_dbg, hipStream_t st)
 {
     const tensair_config &c = m->cfg;
-    tn_launch_build_keys(w.b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, w.epoch, S.keys[0],
-                         S.keys[0] + m->sz.Omax, S.pair_center, negatives_dbg, m->status, st);
+    tn_launch_build_keys(w.b, c.vocab, m->thr, m->alias, c.seed, c.worker_id, w.epoch,
+                         (c.flags & TENSAIR_RESAMPLE_NEGATIVES) != 0, S.keys[0], S.keys[0] + m->sz.Omax,
+                         S.pair_center, negatives_dbg, m->status, st);
 }
 
 struct RowIndexDst {

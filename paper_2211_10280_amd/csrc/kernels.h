@@ -31,9 +31,10 @@ struct BatchDesc {
     i64 pair_base;    // pairs_before(begin)
     i64 P;            // pairs in the batch
 };
+// resample: a negative equal to the pair's center or context word is drawn once more (words 2, 3)
 void tn_launch_build_keys(const BatchDesc &b, i64 V, const u32 *thr, const int *alias, u64 seed,
-                          u32 worker, u32 epoch, u32 *out_keys, u32 *in_keys, int *pair_center,
-                          int *neg_dbg, int *status, hipStream_t st);
+                          u32 worker, u32 epoch, bool resample, u32 *out_keys, u32 *in_keys,
+                          int *pair_center, int *neg_dbg, int *status, hipStream_t st);
 
 // ---- stage 2: stable LSD radix sort of (key, value) for two independent problems at once
 struct RadixProb {

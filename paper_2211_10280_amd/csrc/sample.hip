@@ -63,7 +63,7 @@ void tn_launch_init_tables(void *w_in, void *w_out, i64 V, int D, int stride, in
 // are the negatives.  Writes the out-side key list [pair][N+1] (pair-major, the order of
 // the occurrence list), the in-side key of every center, and the center token of every pair.
 __global__ void k_build_keys(BatchDesc b, i64 V, const u32 *__restrict__ thr,
-                             const int *__restrict__ alias, u32 k0, u32 k1, u32 ctr3,
+                             const int *__restrict__ alias, u32 k0, u32 k1, u32 ctr3, int resample,
                              u32 *__restrict__ out_keys, u32 *__restrict__ in_keys,
                              int *__restrict__ pair_center, int *__restrict__ neg_dbg,
                              int *__restrict__ status)
@@ -98,31 +98,36 @@ __global__ void k_build_keys(BatchDesc b, i64 V, const u32 *__restrict__ thr,
         o = (i64)q - b.w + 1;
     }
     i64 pair = pairs_before(p, b.T, b.w) - b.pair_base + rank;
+    int ctx = b.tok[p + o];
+    if ((u32)ctx >= (u32)V) {
+        ctx = 0;
+        atomicOr(status, ST_BAD_ID);
+    }
     int id;
     if (k == 0) {
-        id = b.tok[p + o];
-        if ((u32)id >= (u32)V) {
-            id = 0;
-            atomicOr(status, ST_BAD_ID);
-        }
+        id = ctx;
         pair_center[pair] = c;
     } else {
         philox_out r = philox4x32_10((u32)((u64)p & 0xFFFFFFFFu), (u32)((u64)p >> 32),
                                      (u32)q * 65536u + (u32)(k - 1), ctr3, k0, k1);
         u32 bkt = (u32)(((u64)r.r0 * (u64)V) >> 32);
         id = (r.r1 < thr[bkt]) ? (int)bkt : alias[bkt];
+        if (resample && (id == c || id == ctx)) {   // the variant: one more draw from the block's other two words
+            bkt = (u32)(((u64)r.r2 * (u64)V) >> 32);
+            id = (r.r3 < thr[bkt]) ? (int)bkt : alias[bkt];
+        }
         if (neg_dbg) neg_dbg[pair * b.N + (k - 1)] = id;
     }
     out_keys[pair * Np1 + k] = (u32)id;
 }
 
 void tn_launch_build_keys(const BatchDesc &b, i64 V, const u32 *thr, const int *alias, u64 seed,
-                          u32 worker, u32 epoch, u32 *out_keys, u32 *in_keys, int *pair_center,
-                          int *neg_dbg, int *status, hipStream_t st)
+                          u32 worker, u32 epoch, bool resample, u32 *out_keys, u32 *in_keys,
+                          int *pair_center, int *neg_dbg, int *status, hipStream_t st)
 {
     i64 total = (i64)b.n_centers * 2 * b.w * (b.N + 1);
     int blocks = (int)((total + BLOCK - 1) / BLOCK);
     hipLaunchKernelGGL(k_build_keys, dim3(blocks), dim3(BLOCK), 0, st, b, V, thr, alias,
                        (u32)(seed & 0xFFFFFFFFu), (u32)(seed >> 32), worker + 65536u * epoch,
-                       out_keys, in_keys, pair_center, neg_dbg, status);
+                       resample ? 1 : 0, out_keys, in_keys, pair_center, neg_dbg, status);
 }

@@ -33,15 +33,16 @@ class DasgdWorker:
         self.announced = -1          # last step whose mini-batch has been announced
         self.device = device
         dt = B.F32 if cfg.dtype == "f32" else B.BF16
+        flags = B.RESAMPLE_NEGATIVES if cfg.resample else 0
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
         self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
                              max(cfg.peers, 0), cfg.seed, counts, worker_id=0, row_stride=row_stride,
-                             device=device)
+                             device=device, flags=flags)
         # a second handle computes the peers' gradients on snapshots (its tables are rebound per call)
         self.peer_model = None
         if cfg.peers > 0:
             self.peer_model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch, 0,
-                                      cfg.seed, counts, worker_id=1, row_stride=row_stride,
+                                      cfg.seed, counts, worker_id=1, row_stride=row_stride, flags=flags,
                                       tables=(self.model.w_in, self.model.w_out), device=device)
         self.own = self.model.grad_buffers()
         self.peer_bufs = [self.model.grad_buffers() for _ in range(cfg.peers)]

@@ -40,6 +40,7 @@ class Config:
     lr: float           # alpha of Eq. 1
     parity_steps: int   # steps the multi-step parity runs use
     grad_buffer: int = 1   # maxGradBuffer of Algorithm 1: own gradients summed per broadcast
+    resample: bool = False   # variant: a negative equal to the pair's center or context is drawn once more
 
     # seeds: one per purpose so that changing one input does not move another
     @property

@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
         pytest.fail("libtensair.so has not been built (python -m paper_2211_10280_amd.build)")
     L = C.CDLL(B.LIB_PATH)
     names = _declared()
-    assert len(names) >= 13
+    assert len(names) >= 24
     for n in names:
         assert hasattr(L, n), n
     assert sorted(B.SYMBOLS) == names        # the binding forwards to exactly these
@@ -35,13 +35,15 @@ def test_host_side_argument_checks():
     assert B.tensair_capacity_in(good, 64) == 64
     assert B.tensair_capacity_out(good, 64) == 1000          # min(V, 2*2*64*6 = 1536)
     assert B.tensair_capacity_out(good, 10) == 240
+    assert B.tensair_workspace_bytes(B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7, B.RESAMPLE_NEGATIVES)) > 0
     for bad in (B.Config(0, 32, 32, B.F32, 2, 5, 64, 0, 0, 7),      # vocab
                 B.Config(1000, 30, 32, B.F32, 2, 5, 64, 0, 0, 7),    # dim not a multiple of 4
                 B.Config(1000, 32, 28, B.F32, 2, 5, 64, 0, 0, 7),    # stride < dim
                 B.Config(1000, 32, 32, 5, 2, 5, 64, 0, 0, 7),        # dtype
                 B.Config(1000, 32, 32, B.F32, 0, 5, 64, 0, 0, 7),    # window
                 B.Config(1000, 32, 32, B.F32, 2, 5, 64, 32, 0, 7),   # too many peers
-                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 70000, 7)):  # worker id
+                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 70000, 7),   # worker id
+                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7, 2)):   # unknown flag
         with pytest.raises(B.TensairError):
             B.tensair_workspace_bytes(bad)
     assert L.tensair_last_error()                                # a message is left behind

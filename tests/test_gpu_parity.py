@@ -101,17 +101,36 @@ GRAD_CASES = [
 
 @pytest.mark.parametrize("case", GRAD_CASES, ids=lambda c: f"V{c[0]}_D{c[1]}_B{c[7]}_{c[9]}")
 def test_sgns_grad_parity(case):
+    _grad_parity(case)
+
+
+@pytest.mark.parametrize("case", [
+    (30, 32, 32, 5_000, 1.2, 3, 6, 200, 50, "f32"),             # a third of the draws collide
+    (3, 64, 64, 5_000, 0.5, 3, 4, 700, 100, "f32"),             # three words: most second draws collide again
+    (5000, 300, 300, 40_000, 1.1, 5, 10, 512, 1024, "f32"),
+    (2000, 512, 512, 30_000, 1.05, 5, 10, 256, 4096, "bf16"),
+], ids=lambda c: f"V{c[0]}_D{c[1]}_B{c[7]}_{c[9]}")
+def test_sgns_grad_parity_with_resampled_negatives(case):
+    """The variant in which a negative equal to the pair's center or context word is drawn once more."""
+    _grad_parity(case, resample=True)
+
+
+def _grad_parity(case, resample=False):
     V, D, stride, T, zs, w, N, Bc, begin, dtype = case
-    _say("grad case", case)
+    _say("grad case", case, "resampled negatives" if resample else "")
     bd, od, tdt, _ = DT[dtype]
     tok = W.zipf_stream(V, zs, T, 5)
     counts = W.unigram_counts(tok, V)
     Wi, Wo = _random_tables(V, D, stride, dtype, seed=V + D)
     d_in, d_out = _tables_to_dev(Wi, dtype), _tables_to_dev(Wo, dtype)
-    m = B.Model(V, D, bd, w, N, Bc, 0, 0xC0FFEE, counts, worker_id=3, row_stride=stride, tables=(d_in, d_out))
+    m = B.Model(V, D, bd, w, N, Bc, 0, 0xC0FFEE, counts, worker_id=3, row_stride=stride, tables=(d_in, d_out),
+                flags=B.RESAMPLE_NEGATIVES if resample else 0)
     thr, alias = oracle.alias_build(counts)
-    og = oracle.sgns_grad(tok, w, N, begin, Bc, D, od, Wi, Wo, thr, alias, 0xC0FFEE, 3, 2)
+    og = oracle.sgns_grad(tok, w, N, begin, Bc, D, od, Wi, Wo, thr, alias, 0xC0FFEE, 3, 2, resample=resample)
     P = og.P
+    if resample and V <= 30:      # the variant does something here
+        pos, q = oracle.pairs(T, w, begin, Bc)
+        assert (og.negatives != oracle.sample_negatives(V, thr, alias, 0xC0FFEE, 3, 2, pos, q, N)).any()
     assert m.pair_count(T, begin, Bc) == P
 
     dtok = torch.from_numpy(tok).cuda()
@@ -367,6 +386,14 @@ def test_train_full_size_configs(idx, steps):
     """Configurations 2-5 at their full sizes, in the launch configuration the benchmark times."""
     _say("train full size", idx)
     _run_both(W.CONFIGS[idx], steps)
+
+
+@pytest.mark.parametrize("prefetch", [True, False], ids=["prefetch", "inline"])
+def test_train_with_resampled_negatives(prefetch):
+    """Training with the resampling variant on a vocabulary small enough for collisions in every mini-batch."""
+    cfg = W.CONFIGS[2].scaled(name="cfg2_resample", vocab=400, tokens=100_000, batch=256, resample=True)
+    _say("train with resampled negatives", cfg.name)
+    _run_both(cfg, 8, prefetch=prefetch)
 
 
 @pytest.mark.parametrize("idx,n,steps", [(2, 1, 9), (3, 1, 7), (3, 2, 6), (5, 1, 5)])

@@ -121,6 +121,54 @@ def test_negatives_do_not_depend_on_batching():
     assert np.array_equal(run(64), run(7))
 
 
+def test_resampled_negatives_by_hand_and_by_their_statistics():
+    """The variant that draws a colliding negative once more: every entry recomputed step by step from the
+    Philox block (first draw from words 0/1; if it equals the pair's center or context word, the draw from
+    words 2/3), on a vocabulary small enough for collisions to be common; without a collision it is the base
+    draw; collisions become rarer by about the collision probability itself."""
+    V, T, w, N = 6, 300, 2, 5
+    rng = np.random.default_rng(5)
+    tok = rng.integers(0, V, size=T).astype(np.int32)
+    counts = np.bincount(tok, minlength=V).astype(np.uint64)
+    thr, alias = oracle.alias_build(counts)
+    seed, worker, epoch = 0x1122334455667788, 2, 1
+    pos, q = oracle.pairs(T, w, 0, T)
+    base = oracle.sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N)
+    got = oracle.sample_negatives(V, thr, alias, seed, worker, epoch, pos, q, N, resample_tok=tok, w=w)
+
+    def pick(r_bucket, r_accept):
+        b = (int(r_bucket) * V) >> 32
+        return b if int(r_accept) < int(thr[b]) else int(alias[b])
+
+    hits_before = hits_after = 0
+    for i in range(0, pos.size, 7):             # a seventh of the pairs, every slot
+        p, qq = int(pos[i]), int(q[i])
+        o = qq - w if qq < w else qq - w + 1
+        center, context = int(tok[p]), int(tok[p + o])
+        for k in range(N):
+            r = oracle.philox4x32_10([p & 0xFFFFFFFF, p >> 32, qq * 65536 + k, worker + 65536 * epoch],
+                                     [seed & 0xFFFFFFFF, seed >> 32])
+            first = pick(r[0], r[1])
+            want = pick(r[2], r[3]) if first in (center, context) else first
+            assert int(got[i, k]) == want and int(base[i, k]) == first
+    o_all = np.where(q < w, q - w, q - w + 1)
+    cen, ctx = tok[pos][:, None], tok[pos + o_all][:, None]
+    hits_before = int(((base == cen) | (base == ctx)).sum())
+    hits_after = int(((got == cen) | (got == ctx)).sum())
+    same = (base != cen) & (base != ctx)
+    assert np.array_equal(got[same], base[same])          # no collision: the base draw
+    assert hits_before > 0.2 * base.size                  # collisions are common here ...
+    assert hits_after < 0.6 * hits_before                 # ... and the second draw removes most of them
+    # the gradient routine with the variant switched on uses exactly these negatives
+    D = 4
+    W_in = (rng.standard_normal((V, D)) * 0.3).astype(np.float32)
+    W_out = (rng.standard_normal((V, D)) * 0.3).astype(np.float32)
+    g = oracle.sgns_grad(tok, w, N, 10, 40, D, oracle.F32, W_in, W_out, thr, alias, seed, worker, epoch, resample=True)
+    p2, q2 = oracle.pairs(T, w, 10, 40)
+    assert np.array_equal(g.negatives, oracle.sample_negatives(V, thr, alias, seed, worker, epoch, p2, q2, N,
+                                                               resample_tok=tok, w=w))
+
+
 # ------------------------------------------------------------------ pairs
 @pytest.mark.parametrize("T,w", [(1, 2), (2, 3), (5, 2), (20, 3), (20, 8), (7, 10)])
 def test_pairs_brute_force_and_closed_form(T, w):
