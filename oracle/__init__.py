@@ -68,6 +68,8 @@ def lib():
         L.orc_grad_free.restype = None
         L.orc_dasgd_apply_table.argtypes = [i64, i32, i32, C.c_int, vp, i32, vp, vp, vp, C.c_float]
         L.orc_dasgd_apply_table.restype = None
+        L.orc_dasgd_apply_table_sr.argtypes = [i64, i32, i32, C.c_int, vp, i32, vp, vp, vp, C.c_float, u64, u32, u32]
+        L.orc_dasgd_apply_table_sr.restype = None
         L.orc_double_to_bf16.argtypes = [C.c_double]
         L.orc_double_to_bf16.restype = C.c_uint16
         _lib = L
@@ -192,10 +194,12 @@ def sgns_grad(tok, w, N, begin, n_centers, D, dtype, W_in, W_out, thr, alias,
 
 
 # ---------------------------------------------------------------- apply
-def dasgd_apply_table(W, D, dtype, sources, lr):
+def dasgd_apply_table(W, D, dtype, sources, lr, stochastic=None):
     """apply_gradient of Algorithm 1 / Eq. 1 on one table, in place.
     ``sources`` = list of (ids int32[U_k], rows float32[U_k, D]); source 0 is the own
-    gradient, the others are peers' (same alpha, summed)."""
+    gradient, the others are peers' (same alpha, summed).
+    ``stochastic`` = (seed, serial, table): the variant in which a bfloat16 table is rounded
+    stochastically (see ``stochastic_bf16`` in the C source); ignored for float tables."""
     V, stride = W.shape
     assert W.dtype == _NP[dtype] and W.flags.c_contiguous
     K = len(sources)
@@ -204,13 +208,20 @@ def dasgd_apply_table(W, D, dtype, sources, lr):
     n = np.array([i.shape[0] for i in ids], dtype=np.int64)
     idp = (C.c_void_p * max(K, 1))(*[i.ctypes.data for i in ids])
     rwp = (C.c_void_p * max(K, 1))(*[r.ctypes.data for r in rows])
-    lib().orc_dasgd_apply_table(V, D, stride, dtype, _p(W), K, _p(n), idp, rwp, np.float32(lr))
+    if stochastic is None:
+        lib().orc_dasgd_apply_table(V, D, stride, dtype, _p(W), K, _p(n), idp, rwp, np.float32(lr))
+    else:
+        seed, serial, table = stochastic
+        lib().orc_dasgd_apply_table_sr(V, D, stride, dtype, _p(W), K, _p(n), idp, rwp, np.float32(lr),
+                                       seed, serial, table)
 
 
-def dasgd_apply(W_in, W_out, D, dtype, grads, lr):
-    """Merged application of the own gradient grads[0] and peer gradients grads[1:]."""
-    dasgd_apply_table(W_in, D, dtype, [(g.gin.ids, g.gin.rows) for g in grads], lr)
-    dasgd_apply_table(W_out, D, dtype, [(g.gout.ids, g.gout.rows) for g in grads], lr)
+def dasgd_apply(W_in, W_out, D, dtype, grads, lr, stochastic=None):
+    """Merged application of the own gradient grads[0] and peer gradients grads[1:].
+    ``stochastic`` = (seed, serial): stochastic rounding of bfloat16 tables (a variant)."""
+    sr = (lambda t: None) if stochastic is None else (lambda t: (stochastic[0], stochastic[1], t))
+    dasgd_apply_table(W_in, D, dtype, [(g.gin.ids, g.gin.rows) for g in grads], lr, sr(0))
+    dasgd_apply_table(W_out, D, dtype, [(g.gout.ids, g.gout.rows) for g in grads], lr, sr(1))
 
 
 # ---------------------------------------------------------------- gradient buffer

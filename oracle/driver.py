@@ -93,7 +93,9 @@ class OracleWorker:
         if self.bf16_messages:       # what is sent is rounded once, after any summing in the sender's buffer
             grads = [grads[0]] + [oracle.grad_through_bf16(g) for g in grads[1:]]
         t0 = time.perf_counter()
-        oracle.dasgd_apply(self.W_in, self.W_out, c.dim, self.dtype, grads, c.lr)
+        # stochastic rounding (variant): the serial number of this worker's table update is its step number
+        oracle.dasgd_apply(self.W_in, self.W_out, c.dim, self.dtype, grads, c.lr,
+                           stochastic=(c.seed, t) if c.stochastic_rounding else None)
         self.t_apply = time.perf_counter() - t0
         self.applied |= {(t, k) for k in range(c.peers + 1)}
         self.last_own, self.last_peers = grads[0], grads[1:]

@@ -444,9 +444,34 @@ void orc_grad_free(orc_grad *G)
  * are merged: G[r] = sum_k g_k[r] in double, then one rounded store
  * W[r] = round(W[r] - alpha*G[r]).  Rows outside the union are not written.
  * alpha is a float on the interface; it enters as (double)(float)lr.            */
-void orc_dasgd_apply_table(int64_t V, int32_t D, int32_t stride, int dtype, void *W,
-                           int32_t n_src, const int64_t *n_rows,
-                           const int32_t *const *ids, const float *const *rows, float lr)
+/* sr != 0: the variant with stochastic rounding of bfloat16 tables (the paper leaves the
+ * rounding open; the base reading is round-to-nearest-even).  The new value is taken
+ * to single precision (nearest even), 16 random bits are added to its bit pattern below
+ * the bfloat16 mantissa and the result is truncated, so the value goes up with
+ * probability (discarded bits)/2^16 and the expectation is the single-precision value.
+ * The bits of element i = row*D + col are the low half of word (i mod 4) of
+ * Philox(counter = (i/4 low, i/4 high, serial, 'SRND' + table), key = seed); serial
+ * counts the model's table updates, table is 0 for W_in and 1 for W_out.  Infinities
+ * and NaN are kept.                                                                  */
+static uint16_t stochastic_bf16(double x, uint64_t seed, uint32_t serial, uint32_t table, uint64_t i)
+{
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u)
+        return (uint16_t)((u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u));
+    uint64_t blk = i >> 2;
+    uint32_t ctr[4] = { (uint32_t)(blk & 0xFFFFFFFFu), (uint32_t)(blk >> 32), serial, 0x53524E44u + table };
+    uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return (uint16_t)((u + (out[i & 3] & 0xFFFFu)) >> 16);
+}
+
+static void apply_table(int64_t V, int32_t D, int32_t stride, int dtype, void *W,
+                        int32_t n_src, const int64_t *n_rows,
+                        const int32_t *const *ids, const float *const *rows, float lr,
+                        int sr, uint64_t seed, uint32_t serial, uint32_t table)
 {
     rowacc acc;
     rowacc_init(&acc, V, D);
@@ -463,8 +488,27 @@ void orc_dasgd_apply_table(int64_t V, int32_t D, int32_t stride, int dtype, void
         const double *g = acc.rows + (size_t)s * D;
         for (int32_t d = 0; d < D; ++d) {
             int64_t at = r * (int64_t)stride + d;
-            tab_set(W, dtype, at, tab_get(W, dtype, at) - alpha * g[d]);
+            double nv = tab_get(W, dtype, at) - alpha * g[d];
+            if (sr && dtype == ORC_BF16)
+                ((uint16_t *)W)[at] = stochastic_bf16(nv, seed, serial, table, (uint64_t)r * (uint64_t)D + (uint64_t)d);
+            else
+                tab_set(W, dtype, at, nv);
         }
     }
     rowacc_free(&acc);
+}
+
+void orc_dasgd_apply_table(int64_t V, int32_t D, int32_t stride, int dtype, void *W,
+                           int32_t n_src, const int64_t *n_rows,
+                           const int32_t *const *ids, const float *const *rows, float lr)
+{
+    apply_table(V, D, stride, dtype, W, n_src, n_rows, ids, rows, lr, 0, 0, 0, 0);
+}
+
+void orc_dasgd_apply_table_sr(int64_t V, int32_t D, int32_t stride, int dtype, void *W,
+                              int32_t n_src, const int64_t *n_rows,
+                              const int32_t *const *ids, const float *const *rows, float lr,
+                              uint64_t seed, uint32_t serial, uint32_t table)
+{
+    apply_table(V, D, stride, dtype, W, n_src, n_rows, ids, rows, lr, 1, seed, serial, table);
 }

@@ -41,6 +41,7 @@ class Config:
     parity_steps: int   # steps the multi-step parity runs use
     grad_buffer: int = 1   # maxGradBuffer of Algorithm 1: own gradients summed per broadcast
     resample: bool = False   # variant: a negative equal to the pair's center or context is drawn once more
+    stochastic_rounding: bool = False   # variant: bf16 tables are rounded stochastically by the table update
 
     # seeds: one per purpose so that changing one input does not move another
     @property

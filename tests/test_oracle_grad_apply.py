@@ -483,3 +483,67 @@ def test_bf16_messages_move_the_update_by_at_most_their_rounding():
                     oracle.SparseRows(srcs[2][0], srcs[2][1], np.zeros(41, np.int64)))
     h = oracle.grad_through_bf16(g)
     assert h.P == 3 and np.array_equal(h.gin.ids, g.gin.ids) and np.array_equal(h.gout.rows, through[2][1])
+
+
+# ------------------------------------------------------------------ stochastic rounding of bf16 tables
+def test_stochastic_rounding_by_hand_neighbours_and_expectation():
+    """The variant of Eq. 1's store for bfloat16 tables: one decision recomputed from the Philox block; every
+    result is one of the two bfloat16 neighbours of the exact value; an exactly representable result never
+    moves; the mean over many draws is the exact value (where round-to-nearest loses the whole update);
+    same serial reproduces, another serial decides anew; float tables ignore it."""
+    V, D, lr, seed = 64, 8, 0.025, 0xFEEDFACE12345678
+    rng = np.random.default_rng(21)
+    W0 = oracle.grad_pack_rows((rng.standard_normal((V, D)) * 0.5).astype(np.float32))     # a bfloat16 table
+    ids = np.sort(rng.choice(V, 40, replace=False)).astype(np.int32)
+    g = (rng.standard_normal((40, D)) * 0.3).astype(np.float32)
+    exact = oracle.bf16_to_f32(W0).astype(np.float64)
+    exact[ids] -= float(np.float32(lr)) * g.astype(np.float64)
+    X = W0.copy()
+    oracle.dasgd_apply_table(X, D, oracle.BF16, [(ids, g)], lr, stochastic=(seed, 5, 1))
+    # by hand: element (row, col) of table 1 at serial 5
+    row, col = int(ids[7]), 3
+    i = row * D + col
+    r = oracle.philox4x32_10([(i >> 2) & 0xFFFFFFFF, (i >> 2) >> 32, 5, 0x53524E44 + 1], [seed & 0xFFFFFFFF, seed >> 32])
+    u = int(np.float32(exact[row, col]).view(np.uint32))
+    assert int(X[row, col]) == ((u + (int(r[i & 3]) & 0xFFFF)) >> 16) & 0xFFFF
+    # neighbours: truncation towards zero of the single-precision value, or one step away from zero
+    f32 = exact.astype(np.float32)
+    down = (f32.view(np.uint32) >> 16).astype(np.uint16)
+    assert (((X == down) | (X == down + 1))).all()
+    untouched = np.setdiff1d(np.arange(V), ids)
+    assert np.array_equal(X[untouched], W0[untouched])
+    # representable results stay: gradient 0, and a gradient that moves the value by exactly one bfloat16 step
+    Z = W0.copy()
+    oracle.dasgd_apply_table(Z, D, oracle.BF16, [(ids, np.zeros_like(g))], lr, stochastic=(seed, 6, 0))
+    assert np.array_equal(Z, W0)
+    # expectation: 1.0 - alpha * 0.01 is a quarter of the way down to the next bfloat16 below 1 (spacing 2^-8)
+    ones = np.full((V, D), 0x3F80, np.uint16)
+    allids = np.arange(V, dtype=np.int32)
+    small = np.full((V, D), 0.01, np.float32)
+    total, n = 0.0, 300
+    for serial in range(n):
+        Y = ones.copy()
+        oracle.dasgd_apply_table(Y, D, oracle.BF16, [(allids, small)], lr, stochastic=(seed, serial, 0))
+        assert set(np.unique(Y)) <= {0x3F80, 0x3F7F}
+        total += float(oracle.bf16_to_f32(Y).astype(np.float64).mean())
+    want = 1.0 - float(np.float32(lr)) * float(np.float32(0.01))
+    step = 2.0 ** -8                                     # distance between the two candidates
+    p = (1.0 - want) / step                              # probability of the lower one
+    sd = step * np.sqrt(p * (1 - p) / (n * V * D))
+    assert abs(total / n - want) < 6 * sd
+    Y = ones.copy()
+    oracle.dasgd_apply_table(Y, D, oracle.BF16, [(allids, small)], lr)
+    assert (Y == 0x3F80).all()                           # nearest-even: the update is lost
+    # reproducible per serial, different across serials and tables
+    A, Bt, Ct, Dt = ones.copy(), ones.copy(), ones.copy(), ones.copy()
+    oracle.dasgd_apply_table(A, D, oracle.BF16, [(allids, small)], lr, stochastic=(seed, 9, 0))
+    oracle.dasgd_apply_table(Bt, D, oracle.BF16, [(allids, small)], lr, stochastic=(seed, 9, 0))
+    oracle.dasgd_apply_table(Ct, D, oracle.BF16, [(allids, small)], lr, stochastic=(seed, 10, 0))
+    oracle.dasgd_apply_table(Dt, D, oracle.BF16, [(allids, small)], lr, stochastic=(seed, 9, 1))
+    assert np.array_equal(A, Bt) and not np.array_equal(A, Ct) and not np.array_equal(A, Dt)
+    # float tables: the flag changes nothing
+    F1 = oracle.bf16_to_f32(W0).copy()
+    F2 = F1.copy()
+    oracle.dasgd_apply_table(F1, D, oracle.F32, [(ids, g)], lr)
+    oracle.dasgd_apply_table(F2, D, oracle.F32, [(ids, g)], lr, stochastic=(seed, 5, 1))
+    assert np.array_equal(F1, F2)
