@@ -52,6 +52,10 @@ def main():
     ap.add_argument("--row-stride", type=int, default=None,
                     help="elements between table rows (default: dim; a multiple of 32 fp32 / 64 bf16 elements "
                          "starts every row on a 128-byte line)")
+    ap.add_argument("--stochastic-rounding", action="store_true",
+                    help="bf16 tables rounded stochastically by the table update (a variant; workload 5)")
+    ap.add_argument("--resample-negatives", action="store_true",
+                    help="negatives equal to the pair's center or context word drawn once more (a variant)")
     ap.add_argument("--breakdown", action="store_true", help="extra pass with an event after every stage (stderr)")
     ap.add_argument("--peer-payload", choices=["f32", "bf16"], default="f32",
                     help="f32: the peers' gradients as the paper sends them (the metric); bf16: as bfloat16 messages "
@@ -71,6 +75,8 @@ def main():
     from paper_2211_10280_amd.trainer import DasgdWorker
 
     cfg = W.CONFIGS[args.config]
+    if args.stochastic_rounding or args.resample_negatives:
+        cfg = cfg.scaled(stochastic_rounding=args.stochastic_rounding, resample=args.resample_negatives)
     if args.steps is None:
         args.steps = {1: 100, 2: 50, 3: 20, 4: 10, 5: 6}[cfg.idx]   # bounded by the HBM the stored peers take
     if args.warmup is None:
@@ -209,7 +215,8 @@ def main():
                    "negatives": cfg.negatives, "batch_centers": cfg.batch, "peers": K,
                    "max_stale": cfg.max_stale, "zipf_s": cfg.zipf_s, "pairs_per_step": n_pairs / S,
                    "next_batch_prefetch": not args.no_prefetch,
-                   "row_stride": model.cfg.row_stride, "peer_payload": args.peer_payload},
+                   "row_stride": model.cfg.row_stride, "peer_payload": args.peer_payload,
+                   "stochastic_rounding": cfg.stochastic_rounding, "resampled_negatives": cfg.resample},
         "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
         "measured_copy_GBps": copy_GBps,
         "step_algorithmic_bytes": step_bytes / S,

@@ -68,7 +68,7 @@ typedef struct {
     int32_t max_peers;   /* largest number of peer gradients a call may pass, <= TENSAIR_MAX_PEERS */
     uint32_t worker_id;  /* < 65536; enters the negative-sampling counter (peers differ by it) */
     uint64_t seed;       /* key of the counter-based generator (negatives and table init) */
-    uint32_t flags;      /* 0, or TENSAIR_RESAMPLE_NEGATIVES */
+    uint32_t flags;      /* 0, or TENSAIR_RESAMPLE_NEGATIVES | TENSAIR_STOCHASTIC_ROUNDING */
 } tensair_config;
 
 /* A variant the paper leaves open (it does not say what happens to a negative that equals the pair's
@@ -77,6 +77,19 @@ typedef struct {
  * multiply-high of word 2, word 3 against the threshold), and the second draw is kept whatever it
  * is.  Still a pure function of the counter, with fixed shapes. */
 #define TENSAIR_RESAMPLE_NEGATIVES 1u
+
+/* Another variant the paper leaves open (it does not say how a low-precision table is rounded; by
+ * default round-to-nearest-even, which drops every update below half a unit in the last place): with
+ * this flag the table update of a bf16 model (tensair_dasgd_apply, tensair_step and their _packed
+ * forms) rounds stochastically.  The new value W[r] - lr * sum, in fp32, gets 16 random bits added
+ * to its bit pattern below the bfloat16 mantissa and is truncated, so it goes up with probability
+ * (discarded bits)/2^16 and its expectation is the fp32 value; infinities and NaN are kept.  The
+ * bits of element i = r*dim + col are the low half of word (i mod 4) of Philox4x32-10(counter =
+ * (i/4 low, i/4 high, serial, 'SRND' + table), key = seed), table = 0 for W_in, 1 for W_out; serial
+ * counts the table updates enqueued on this model handle since tensair_model_init, from 0 (calls
+ * that update nothing do not count).  Reproducible for a given sequence of calls.  No effect on
+ * fp32 tables. */
+#define TENSAIR_STOCHASTIC_ROUNDING 2u
 
 /* One table's sparse gradient: the rows a mini-batch touches (Section 4, "Sparse vs.
  * Dense Models").  All pointers DEVICE, caller-owned.  row_ids[0..*n_rows) is strictly

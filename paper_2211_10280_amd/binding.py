@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 OK, EINVAL, ECAPACITY, EHIP, EDATA = 0, -1, -2, -3, -4
 MAX_PEERS = 31
 RESAMPLE_NEGATIVES = 1
+STOCHASTIC_ROUNDING = 2
 
 SYMBOLS = [
     "tensair_workspace_bytes", "tensair_capacity_in", "tensair_capacity_out", "tensair_model_init",

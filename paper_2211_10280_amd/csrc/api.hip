@@ -58,7 +58,7 @@ bool config_ok(const tensair_config *c, const char **why)
     if (c->max_centers < 1) { *why = "max_centers must be positive"; return false; }
     if (c->max_peers < 0 || c->max_peers > TENSAIR_MAX_PEERS) { *why = "max_peers out of range"; return false; }
     if (c->worker_id >= 65536u) { *why = "worker_id must be below 65536"; return false; }
-    if (c->flags & ~TENSAIR_RESAMPLE_NEGATIVES) { *why = "unknown flag"; return false; }
+    if (c->flags & ~(TENSAIR_RESAMPLE_NEGATIVES | TENSAIR_STOCHASTIC_ROUNDING)) { *why = "unknown flag"; return false; }
     i64 omax = (i64)2 * c->window * c->max_centers * (c->negatives + 1);
     if (omax + c->max_centers >= 0x7FFFFFFFLL) { *why = "batch too large: occurrences must fit 31 bits"; return false; }
     return true;
@@ -156,6 +156,7 @@ struct tensair_model {
     const ApplyArgs *fused_apply = nullptr;
     bool fused_index_done = false;
     bool prepare_under_apply = false;   // tensair_step: the table update is long enough to hide a preparation
+    u32 apply_serial = 0;               // table updates enqueued so far (stochastic rounding draws from it)
     // stage timing (tensair_profile): events recorded on the caller's stream
     int prof_level = 0;
     std::vector<hipEvent_t> prof_pool;
@@ -797,6 +798,10 @@ static int make_apply_args(tensair_model *m, const tensair_sparse_grad *own, con
     a.lr = lr;
     a.status = m->status;
     a.packed = (packed != nullptr && n_peers > 0) ? 1 : 0;
+    a.sr = ((c.flags & TENSAIR_STOCHASTIC_ROUNDING) && c.dtype == TENSAIR_BF16) ? 1 : 0;
+    a.sr_k0 = (u32)(c.seed & 0xFFFFFFFFu);
+    a.sr_k1 = (u32)(c.seed >> 32);
+    a.sr_serial = m->apply_serial;
     for (int t = 0; t < 2; ++t) {
         a.start[t] = m->start[t];
         a.mask[t] = m->mask[t];
@@ -823,6 +828,7 @@ static int apply_impl(tensair_model *m, const tensair_sparse_grad *own, const te
     tn_launch_apply_index(a, 0, a.n_src, st);
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
+    ++m->apply_serial;
     mark(m, PF_APPLY_UPDATE, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
@@ -960,6 +966,7 @@ static int step_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, 
     }
     mark(m, PF_APPLY_INDEX, st);
     tn_launch_apply_update(a, st);
+    ++m->apply_serial;
     mark(m, PF_APPLY_UPDATE, st);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;

@@ -106,6 +106,20 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 #define APPLY_G 4   // vocabulary rows per wave (measured: 16 -> 4 rows gains 4 %)
 #endif
 
+// Stochastic rounding of one fp32 value to bfloat16: 16 random bits are added below the bfloat16 mantissa
+// and the sum is truncated, so the value goes up with probability (discarded bits)/2^16; infinities and
+// NaN are kept.
+__device__ __forceinline__ u32 sr_bf16(float f, u32 rnd)
+{
+    const u32 u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u);
+    return (u + (rnd & 0xFFFFu)) >> 16;
+}
+struct SrArgs {
+    int on;
+    u32 k0, k1, serial, tag;   // Philox key, counter words 2 and 3 ('SRND' + table)
+};
+
 // Sum of the sources of one row (bits of S, ascending: own first, then peers), W <- W - lr * sum.
 // lane 32*tb + k holds the position `pos` of the row in source k and that source's row pointer.
 // STREAM: the accesses go around the caches (non-temporal), for tables far larger than the caches.  Of a
@@ -119,7 +133,7 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 // take 0.69 ms -- every load was followed by a wait for its data.)
 template <typename T, int ITERS, bool STREAM, bool PACKED>
 __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos, int D, int C4, int lane,
-                                           float neg_lr, int own)
+                                           float neg_lr, int own, u64 chunk0, const SrArgs &sr)
 {
     typedef typename std::conditional<PACKED, bf16_t, float>::type G;
     // table row and source rows stay as loaded (bf16 not yet widened) until every load of the batch is out
@@ -164,6 +178,26 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
         w[it].y = fmaf(neg_lr, acc[it].y, w[it].y);
         w[it].z = fmaf(neg_lr, acc[it].z, w[it].z);
         w[it].w = fmaf(neg_lr, acc[it].w, w[it].w);
+    }
+    if constexpr (sizeof(T) == 2) {
+        if (sr.on) {
+            // the variant: element i = row*D + col takes the low half of word (i mod 4) of
+            // Philox(counter = (i/4 low, i/4 high, serial, 'SRND' + table), key = seed); chunk0 = row*D/4
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int c = lane + WAVE * it;
+                if (c < C4) {
+                    const u64 blk = chunk0 + (u64)c;
+                    const philox_out o = philox4x32_10((u32)blk, (u32)(blk >> 32), sr.serial, sr.tag, sr.k0, sr.k1);
+                    v2u p;
+                    p.x = sr_bf16(w[it].x, o.r0) | (sr_bf16(w[it].y, o.r1) << 16);
+                    p.y = sr_bf16(w[it].z, o.r2) | (sr_bf16(w[it].w, o.r3) << 16);
+                    if (STREAM) __builtin_nontemporal_store(p, (GLOBAL_AS v2u *)(wrow + 4 * c));
+                    else *reinterpret_cast<v2u *>(wrow + 4 * c) = p;
+                }
+            }
+            return;
+        }
     }
     if (STREAM) store_row_s<T, ITERS>(wrow, w, C4, lane);
     else store_row<T, ITERS>(wrow, w, C4, lane);
@@ -242,8 +276,9 @@ k_apply(ApplyArgs a, int nblocks)
             const u32 pos = st + (u32)__popcll(m & ((1ull << b) - 1ull));
             const bool ok = mine && ((m >> b) & 1ull) && (pos < (u32)U);
             const u64 S = __ballot(ok);   // bit 32*tb + k: source k has row r
+            const SrArgs sr = {a.sr, a.sr_k0, a.sr_k1, a.sr_serial, 0x53524E44u + (u32)tb};
             update_row<T, ITERS, STREAM, PACKED>(table + (size_t)r * a.stride, S, rows_ptr, pos, a.D, C4, lane, neg_lr,
-                                                 32 * tb);
+                                                 32 * tb, (u64)r * (u64)C4, sr);
         }
     }
 }

@@ -142,6 +142,9 @@ struct ApplyArgs {
     float lr;
     int *status;
     int packed;              // 1: the peers' rows (sources 1..) are bfloat16 messages, the own gradient's fp32
+    // stochastic rounding of bf16 tables (a variant): key and serial number of this update
+    int sr;
+    u32 sr_k0, sr_k1, sr_serial;
 };
 void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st);
 void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st);

@@ -33,7 +33,7 @@ class DasgdWorker:
         self.announced = -1          # last step whose mini-batch has been announced
         self.device = device
         dt = B.F32 if cfg.dtype == "f32" else B.BF16
-        flags = B.RESAMPLE_NEGATIVES if cfg.resample else 0
+        flags = (B.RESAMPLE_NEGATIVES if cfg.resample else 0) | (B.STOCHASTIC_ROUNDING if cfg.stochastic_rounding else 0)
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
         self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
                              max(cfg.peers, 0), cfg.seed, counts, worker_id=0, row_stride=row_stride,

@@ -43,7 +43,7 @@ def test_host_side_argument_checks():
                 B.Config(1000, 32, 32, B.F32, 0, 5, 64, 0, 0, 7),    # window
                 B.Config(1000, 32, 32, B.F32, 2, 5, 64, 32, 0, 7),   # too many peers
                 B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 70000, 7),   # worker id
-                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7, 2)):   # unknown flag
+                B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7, 4)):   # unknown flag
         with pytest.raises(B.TensairError):
             B.tensair_workspace_bytes(bad)
     assert L.tensair_last_error()                                # a message is left behind
