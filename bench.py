@@ -120,7 +120,9 @@ def main():
         r_out = int(torch.unique(torch.cat(srcs_out)).numel())
         rows_peers = sum(int(x.numel()) for x in srcs_in[1:]) + sum(int(x.numel()) for x in srcs_out[1:])
         bytes_grad.append((ui + uo) * D * e + (ui + uo) * D * 4)
-        bytes_apply.append((ui + uo) * D * 4 + rows_peers * D * peer_elem + 2 * (r_in + r_out) * D * e)
+        # with bfloat16 messages the update also writes the own gradient out as the message this worker sends
+        msg_out = (ui + uo) * D * 2 if peer_elem == 2 else 0
+        bytes_apply.append((ui + uo) * D * 4 + rows_peers * D * peer_elem + 2 * (r_in + r_out) * D * e + msg_out)
         pairs.append(model.pair_count(cfg.tokens, begin, n))
     model.status()
     torch.cuda.synchronize()

@@ -243,14 +243,18 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
  * tensair_dasgd_apply_packed is tensair_dasgd_apply with the peers' gradients given as such
  * messages: W[r] <- W[r] - lr * (own[r] + widen(peer_1[r]) + ... + widen(peer_K[r])), the own
  * gradient still fp32, the sum in fp32 in that order, one rounding on store.
- * tensair_step_packed is tensair_step with packed peers; own_out stays fp32 (pack it to send it). */
+ * tensair_step_packed is tensair_step with packed peers.  own_out stays fp32; with own_msg_out (NULL to
+ * skip; capacities >= tensair_capacity_in/out(n_centers), no buffer shared with own_out) the own
+ * gradient is also written as such a message, bit for bit what tensair_grad_pack makes of own_out,
+ * while its rows pass through the table update -- the message this worker sends, at the cost of
+ * its bytes alone. */
 int tensair_grad_pack(tensair_model *m, const tensair_sparse_grad *g, tensair_packed_grad *out, void *stream);
 int tensair_dasgd_apply_packed(tensair_model *m, const tensair_sparse_grad *own,
                                const tensair_packed_grad *peers, int32_t n_peers, float lr, void *stream);
 int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
                         int32_t n_centers, uint32_t epoch, const tensair_packed_grad *peers,
-                        int32_t n_peers, float lr, tensair_sparse_grad *own_out, float *mean_loss,
-                        void *stream);
+                        int32_t n_peers, float lr, tensair_sparse_grad *own_out,
+                        tensair_packed_grad *own_msg_out, float *mean_loss, void *stream);
 
 /* Announces a coming mini-batch, so that the part of its tensair_sgns_grad / tensair_step
  * call that does not depend on the tables -- pair enumeration, negatives, sort by row id,

@@ -108,7 +108,8 @@ def lib():
         L.tensair_grad_pack.restype = C.c_int
         L.tensair_dasgd_apply_packed.argtypes = L.tensair_dasgd_apply.argtypes
         L.tensair_dasgd_apply_packed.restype = C.c_int
-        L.tensair_step_packed.argtypes = L.tensair_step.argtypes
+        L.tensair_step_packed.argtypes = [vp, vp, i64, i64, i32, u32, C.POINTER(SparseGrad), i32, C.c_float,
+                                          C.POINTER(SparseGrad), C.POINTER(SparseGrad), vp, vp]
         L.tensair_step_packed.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
@@ -288,10 +289,11 @@ def tensair_dasgd_apply_packed(h, own, peers, lr: float, stream=None):
 
 
 def tensair_step_packed(h, tokens, center_begin: int, n_centers: int, epoch: int, peers, lr: float,
-                        own_out: GradBuffers, mean_loss=None, stream=None):
+                        own_out: GradBuffers, own_msg_out=None, mean_loss=None, stream=None):
     arr = _peer_array(peers)
     _check(lib().tensair_step_packed(h, _ptr(tokens), tokens.numel(), center_begin, n_centers, epoch, arr,
-                                     len(peers), C.c_float(lr), C.byref(own_out.c), _ptr(mean_loss),
+                                     len(peers), C.c_float(lr), C.byref(own_out.c),
+                                     C.byref(own_msg_out.c) if own_msg_out is not None else None, _ptr(mean_loss),
                                      _stream(stream)))
 
 
@@ -400,8 +402,8 @@ class Model:
     def dasgd_apply_packed(self, own, peers, lr):
         tensair_dasgd_apply_packed(self.h, own, peers, lr)
 
-    def step_packed(self, tokens, begin, n, epoch, peers, lr, own_out, mean_loss=None):
-        tensair_step_packed(self.h, tokens, begin, n, epoch, peers, lr, own_out, mean_loss)
+    def step_packed(self, tokens, begin, n, epoch, peers, lr, own_out, own_msg_out=None, mean_loss=None):
+        tensair_step_packed(self.h, tokens, begin, n, epoch, peers, lr, own_out, own_msg_out, mean_loss)
 
     def packed_buffers(self, n_centers=None) -> PackedBuffers:
         n = self.cfg.max_centers if n_centers is None else n_centers

@@ -932,13 +932,33 @@ int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensa
 static int step_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
                      int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers,
                      const tensair_packed_grad *packed, int32_t n_peers, float lr, tensair_sparse_grad *own_out,
-                     float *mean_loss, void *stream)
+                     tensair_packed_grad *own_msg, float *mean_loss, void *stream)
 {
     if (!m || !own_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     // validate the apply arguments before anything is enqueued
     ApplyArgs a;
     int rc = make_apply_args(m, own_out, peers, packed, n_peers, lr, a);
     if (rc) return rc;
+    if (own_msg) {   // the own gradient leaves the update as a bfloat16 message as well
+        if (n_centers < 0) return fail(TENSAIR_EINVAL, "n_centers is negative");
+        const tensair_packed_rows *d[2] = {&own_msg->in, &own_msg->out};
+        const tensair_sparse_rows *o[2] = {&own_out->in, &own_out->out};
+        const int64_t need[2] = {tensair_capacity_in(&m->cfg, n_centers), tensair_capacity_out(&m->cfg, n_centers)};
+        for (int t = 0; t < 2; ++t) {
+            if (!d[t]->n_rows || !d[t]->row_ids || !d[t]->row_grads) return fail(TENSAIR_EINVAL, "own_msg: NULL pointer");
+            if ((uintptr_t)d[t]->row_grads & 15) return fail(TENSAIR_EINVAL, "own_msg: rows must be 16-byte aligned");
+            if (d[t]->capacity < need[t])
+                return fail(TENSAIR_ECAPACITY, "own_msg: capacity %lld < %lld rows required", (long long)d[t]->capacity,
+                            (long long)need[t]);
+            if ((const void *)d[t]->row_grads == (const void *)o[t]->row_grads || d[t]->row_ids == o[t]->row_ids ||
+                d[t]->n_rows == o[t]->n_rows)
+                return fail(TENSAIR_EINVAL, "own_msg must not share buffers with own_out");
+            a.msg_rows[t] = d[t]->row_grads;
+            a.msg_ids[t] = d[t]->row_ids;
+            a.msg_n[t] = d[t]->n_rows;
+        }
+        a.packed = 1;   // the kernel that handles messages, also with no peer at all
+    }
     m->fused_apply = &a;
     m->fused_index_done = false;
     {   // rough times of the table update (bytes of the gradient blocks at their largest, at 5 TB/s) and of
@@ -977,16 +997,17 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
                  float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
 {
     return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, peers, nullptr, n_peers, lr, own_out,
-                     mean_loss, stream);
+                     nullptr, mean_loss, stream);
 }
 
 int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
                         int32_t n_centers, uint32_t epoch, const tensair_packed_grad *peers, int32_t n_peers,
-                        float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
+                        float lr, tensair_sparse_grad *own_out, tensair_packed_grad *own_msg_out, float *mean_loss,
+                        void *stream)
 {
     if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
     return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, nullptr, peers, n_peers, lr, own_out,
-                     mean_loss, stream);
+                     own_msg_out, mean_loss, stream);
 }
 
 int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,

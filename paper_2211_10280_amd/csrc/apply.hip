@@ -133,7 +133,7 @@ struct SrArgs {
 // take 0.69 ms -- every load was followed by a wait for its data.)
 template <typename T, int ITERS, bool STREAM, bool PACKED>
 __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos, int D, int C4, int lane,
-                                           float neg_lr, int own, u64 chunk0, const SrArgs &sr)
+                                           float neg_lr, int own, u64 chunk0, const SrArgs &sr, bf16_t *msg_row)
 {
     typedef typename std::conditional<PACKED, bf16_t, float>::type G;
     // table row and source rows stay as loaded (bf16 not yet widened) until every load of the batch is out
@@ -170,6 +170,8 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
 #pragma unroll
         for (int j = 0; j < 4; ++j) add_row_raw<ITERS>(acc, x[j]);
     }
+    // the own row on its way out as a bfloat16 message (its load has long arrived by now)
+    if (PACKED && msg_row != nullptr) store_row_s<bf16_t, ITERS>(msg_row, x0, C4, lane);
     float4 w[ITERS];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -251,6 +253,7 @@ k_apply(ApplyArgs a, int nblocks)
                 U = *s.n_rows;
                 if ((i64)U > s.capacity) U = (int)s.capacity;
                 rows_ptr = (u64)s.rows;
+                if (PACKED && k == 0 && gw == 0 && a.msg_n[tb] != nullptr) *a.msg_n[tb] = U < 0 ? 0 : U;
             }
         }
     }
@@ -277,8 +280,14 @@ k_apply(ApplyArgs a, int nblocks)
             const bool ok = mine && ((m >> b) & 1ull) && (pos < (u32)U);
             const u64 S = __ballot(ok);   // bit 32*tb + k: source k has row r
             const SrArgs sr = {a.sr, a.sr_k0, a.sr_k1, a.sr_serial, 0x53524E44u + (u32)tb};
+            bf16_t *msg_row = nullptr;
+            if (PACKED && a.msg_rows[tb] != nullptr && ((S >> (32 * tb)) & 1ull)) {
+                const u32 at = (u32)rd_lane((int)pos, 32 * tb);          // place of row r in the own gradient
+                msg_row = (bf16_t *)a.msg_rows[tb] + (size_t)at * a.D;
+                if (lane == 32 * tb) a.msg_ids[tb][at] = (int)r;
+            }
             update_row<T, ITERS, STREAM, PACKED>(table + (size_t)r * a.stride, S, rows_ptr, pos, a.D, C4, lane, neg_lr,
-                                                 32 * tb, (u64)r * (u64)C4, sr);
+                                                 32 * tb, (u64)r * (u64)C4, sr, msg_row);
         }
     }
 }

@@ -142,6 +142,10 @@ struct ApplyArgs {
     float lr;
     int *status;
     int packed;              // 1: the peers' rows (sources 1..) are bfloat16 messages, the own gradient's fp32
+    // packed peers only, optional (NULL to skip): the own gradient is also written out as a bfloat16 message
+    // while its rows pass through the update (ids, count and rounded rows; capacity checked on the host)
+    unsigned short *msg_rows[2];
+    int *msg_ids[2], *msg_n[2];
     // stochastic rounding of bf16 tables (a variant): key and serial number of this update
     int sr;
     u32 sr_k0, sr_k1, sr_serial;

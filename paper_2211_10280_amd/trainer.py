@@ -60,8 +60,10 @@ class DasgdWorker:
             self.peer_acc = [[big(), big()] for _ in range(cfg.peers)]
         if bf16_messages:
             n = max(cfg.grad_buffer, 1)
-            self.peer_msgs = [B.PackedBuffers(min(cfg.vocab, n * self.own.cap_in), min(cfg.vocab, n * self.own.cap_out),
-                                              cfg.dim, device) for _ in range(cfg.peers)]
+            msg = lambda: B.PackedBuffers(min(cfg.vocab, n * self.own.cap_in), min(cfg.vocab, n * self.own.cap_out),
+                                          cfg.dim, device)
+            self.peer_msgs = [msg() for _ in range(cfg.peers)]
+            self.own_msg = msg()         # what this worker broadcasts
 
     # -- peers -------------------------------------------------------------
     def _snapshot(self, t):
@@ -119,13 +121,19 @@ class DasgdWorker:
         # prepares it during the step
         if self.prefetch and self.announced == t:
             self._announce(t + 1)
-        packed = len(peers) > 0 and isinstance(peers[0], B.PackedBuffers)
-        (self.model.step_packed if packed else self.model.step)(self.tokens, begin, n, epoch, peers, cfg.lr, self.own,
-                                                                self.mean_loss if want_loss else None)
+        loss = self.mean_loss if want_loss else None
+        if self.bf16_messages:
+            # without a buffer the own gradient is what this worker sends: it leaves the step as a message too
+            msg = self.own_msg if cfg.grad_buffer == 1 else None
+            self.model.step_packed(self.tokens, begin, n, epoch, peers, cfg.lr, self.own, msg, loss)
+        else:
+            self.model.step(self.tokens, begin, n, epoch, peers, cfg.lr, self.own, loss)
         if cfg.grad_buffer > 1:
             self._accumulate(self.own_acc, self.own, t % cfg.grad_buffer == 0)
             if (t + 1) % cfg.grad_buffer == 0:
                 self.sent = self.own_acc[0]      # what this worker would broadcast now
+                if self.bf16_messages:
+                    self.model.grad_pack(self.sent, self.own_msg)
         self.step_no += 1
         if self.prefetch and self.announced < t + 1:
             self._announce(t + 1)

@@ -393,6 +393,15 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
             assert np.array_equal(bi, ow.sent.gin.ids) and np.array_equal(bo, ow.sent.gout.ids), f"step {t}"
             worst_rows = max(worst_rows, rows_rel(br, ow.sent.gin.rows), rows_rel(bq, ow.sent.gout.rows))
     gw.model.status()
+    if bf16_messages and cfg.grad_buffer == 1:
+        # the message this worker broadcast last: its own gradient rounded once -- the oracle's own gradient to
+        # within the gradient's bar plus half a bfloat16 ulp (2^-9 of an element)
+        (mi, mb_in), (mo, mb_out) = gw.own_msg.to_host()
+        og = ow.last_own
+        assert np.array_equal(mi, og.gin.ids) and np.array_equal(mo, og.gout.ids)
+        e = max(rows_rel(oracle.grad_unpack_rows(mb_in), og.gin.rows), rows_rel(oracle.grad_unpack_rows(mb_out), og.gout.rows))
+        _say(f"   own message against the oracle's own gradient: {e:.2e}")
+        assert e <= 2.0 ** -8
     g_in, g_out = gw.tables_to_host()
     _say(f"   {cfg.name}: {steps} steps, worst own-gradient row error {worst_rows:.2e}")
     # bf16: once the two sides' tables differ by a rounding (<= 2 ulp is allowed), the gradients
@@ -591,6 +600,43 @@ def test_grad_pack_parity(V, D, ui, uo):
     assert np.array_equal(ii, gi[0]) and np.array_equal(io, go[0])
     assert np.array_equal(bi, oracle.grad_pack_rows(gi[1])) and np.array_equal(bo, oracle.grad_pack_rows(go[1]))
     assert (msg.in_rows[ui:].cpu().numpy() == 0x1234).all()
+    m.close()
+
+
+@pytest.mark.parametrize("K", [0, 3])
+def test_step_packed_writes_the_own_gradient_as_a_message(K):
+    """tensair_step_packed with own_msg_out: the message equals tensair_grad_pack of own_out bit for bit (and
+    that one equals the oracle's rounding, test_grad_pack_parity), with and without peers; a message buffer
+    that is too small is refused on the host."""
+    cfg = W.CONFIGS[3].scaled(name="cfg3_msg", vocab=20_000, tokens=200_000, batch=300, peers=K)
+    tok, counts = W.make_stream(cfg)
+    dtok = torch.from_numpy(tok).cuda()
+    m = B.Model(cfg.vocab, cfg.dim, B.F32, cfg.window, cfg.negatives, cfg.batch, K, cfg.seed, counts)
+    m.w_out.copy_(m.w_in)
+    peers = []
+    for k in range(K):
+        g = m.grad_buffers()
+        m.sgns_grad(dtok, 1000 * (k + 1), cfg.batch, 0, g)
+        msg = m.packed_buffers()
+        m.grad_pack(g, msg)
+        peers.append(msg)
+    own, own_msg, ref = m.grad_buffers(), m.packed_buffers(), m.packed_buffers()
+    own_msg.in_rows.fill_(0x1234)
+    own_msg.out_rows.fill_(0x1234)
+    m.step_packed(dtok, 5000, cfg.batch, 0, peers, cfg.lr, own, own_msg)
+    m.grad_pack(own, ref)
+    m.status()
+    ui, uo = own.sizes()
+    assert ui > 0 and uo > 0 and own_msg.sizes() == (ui, uo)
+    (ai, ab), (ao, aq) = own_msg.to_host()
+    (bi, bb), (bo, bq) = ref.to_host()
+    assert np.array_equal(ai, bi) and np.array_equal(ao, bo) and np.array_equal(ab, bb) and np.array_equal(aq, bq)
+    assert (own_msg.out_rows[uo:].cpu().numpy() == 0x1234).all()        # nothing beyond the rows that exist
+    small = B.PackedBuffers(own.cap_in, own.cap_out - 1, cfg.dim)
+    with pytest.raises(B.TensairError) as e:
+        m.step_packed(dtok, 5000, cfg.batch, 0, peers, cfg.lr, own, small)
+    assert e.value.code == B.ECAPACITY
+    m.status()
     m.close()
 
 
