@@ -192,6 +192,14 @@ def test_empty_batches():
     m.dasgd_apply(g, [], 0.5)                                     # applying an empty gradient changes nothing
     m.status()
     assert torch.equal(before, m.w_in)
+    # a step on a mini-batch without pairs: empty own gradient, empty message, tables untouched
+    msg = m.packed_buffers()
+    msg.n_rows.fill_(99)
+    g.n_rows.fill_(99)
+    m.step_packed(tok1, 0, 1, 0, [], 0.5, g, msg)
+    m.step(tok1, 0, 1, 0, [], 0.5, g)
+    m.status()
+    assert g.sizes() == (0, 0) and msg.sizes() == (0, 0) and torch.equal(before, m.w_in)
     m.close()
 
 
