@@ -147,10 +147,15 @@ struct tensair_model {
     Prefetched pend;               // prepared (or being prepared) in set 1 - busy
     Prefetched next;               // announced after `pend`: prepared when `pend` is consumed
     hipEvent_t ev_prep = nullptr, ev_reduced = nullptr;
+    // a preparation enqueued beside a gradient calculation may still be running when its mini-batch is
+    // consumed: its keys get an event of their own, so that the forward pass (which only needs the keys)
+    // can start while the sort and the segment scan finish
+    hipEvent_t ev_keys = nullptr;
+    bool pend_late = false;
     bool side_follows = false;     // the second stream has waited for the start of the latest gradient call
     // every event recorded on the second stream takes a ticket; the caller's stream is behind all of
     // them up to main_ticket, so a prepared set with prep_ticket <= main_ticket needs no wait
-    u64 side_ticket = 0, main_ticket = 0, prep_ticket = 0, index_ticket = 0;
+    u64 side_ticket = 0, main_ticket = 0, prep_ticket = 0, index_ticket = 0, keys_ticket = 0;
     // set by tensair_step: the index of the coming apply is built on the second stream, next to
     // the reductions, as soon as the own row ids exist
     const ApplyArgs *fused_apply = nullptr;
@@ -396,6 +401,7 @@ int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_i
         hipEventCreateWithFlags(&m->ev_segs, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_index, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_prep, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->ev_keys, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_reduced, hipEventDisableTiming) != hipSuccess) {
         tensair_model_destroy(m);
         return fail(TENSAIR_EHIP, "model_init: cannot create the side stream");
@@ -545,12 +551,19 @@ static int check_batch(const tensair_model *m, const int32_t *tokens, i64 n_toke
 
 // Enqueue the preparation of an announced mini-batch on the second stream, into the set that the
 // latest gradient call does not read.  The second stream must already be behind that set's last readers.
-static int enqueue_prepare(tensair_model *m, const Prefetched &d)
+// late: the preparation may still be running when the mini-batch is consumed (it was not tucked under a
+// long table update), so its keys are made available on their own.
+static int enqueue_prepare(tensair_model *m, const Prefetched &d, bool late)
 {
     const tensair_config &c = m->cfg;
     BatchSet &S = m->set[1 - m->busy];
     const BatchWork w = batch_work(c, d.tokens, d.n_tokens, d.begin, d.n_centers, d.epoch, d.P);
     enqueue_keys(m, S, w, nullptr, m->side);
+    if (late) {
+        HIP_TRY(hipEventRecord(m->ev_keys, m->side));
+        m->keys_ticket = ++m->side_ticket;
+    }
+    m->pend_late = late;
     const RowIndexDst in = {S.ids_in, S.n_rows, S.off_in, tensair_capacity_in(&c, c.max_centers)};
     const RowIndexDst out = {S.ids_out, S.n_rows + 1, S.off_out, tensair_capacity_out(&c, c.max_centers)};
     enqueue_sort_segments(m, S, w, in, out, m->side, nullptr);
@@ -591,7 +604,7 @@ int tensair_prefetch(tensair_model *m, const int32_t *tokens, int64_t n_tokens, 
         HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
         m->side_follows = true;
     }
-    return enqueue_prepare(m, d);
+    return enqueue_prepare(m, d, true);
 }
 
 int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
@@ -638,10 +651,19 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     // is overwritten, after its preparation has finished
     const int u = 1 - m->busy;
     BatchSet &S = m->set[u];
-    if (m->prep_ticket > m->main_ticket) {
+    // a prepared set that may not be finished yet: the forward pass waits for its keys only, the reductions
+    // for the rest (below); otherwise the caller's stream gets behind the whole preparation here
+    const bool split = prepared && m->pend_late && m->prep_ticket > m->main_ticket;
+    if (split) {
+        if (m->keys_ticket > m->main_ticket) {
+            HIP_TRY(hipStreamWaitEvent(st, m->ev_keys, 0));
+            m->main_ticket = m->keys_ticket;
+        }
+    } else if (m->prep_ticket > m->main_ticket) {
         HIP_TRY(hipStreamWaitEvent(st, m->ev_prep, 0));
         m->main_ticket = m->prep_ticket;
     }
+    const u64 consumed_prep_ticket = m->prep_ticket;   // enqueue_prepare below moves on to the following mini-batch
     m->busy = u;
     m->side_follows = false;
     mark(m, PF_BEGIN_GRAD, st);
@@ -678,10 +700,14 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
         }
         HIP_TRY(hipEventRecord(m->ev_index, m->side));
         m->index_ticket = ++m->side_ticket;
-        if (following.valid && !(fuse && m->prepare_under_apply) && (rc = enqueue_prepare(m, following))) return rc;
         // caller's stream: forward pass on the prepared keys
         tn_launch_forward(f, st);
         if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
+        if (split) {   // the sorted order and the segments of this mini-batch
+            HIP_TRY(hipStreamWaitEvent(st, m->ev_prep, 0));
+            if (consumed_prep_ticket > m->main_ticket) m->main_ticket = consumed_prep_ticket;
+        }
+        if (following.valid && !(fuse && m->prepare_under_apply) && (rc = enqueue_prepare(m, following, true))) return rc;
     } else {
         // 1. keys
         enqueue_keys(m, S, w, negatives_dbg, st);
@@ -772,7 +798,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     if (following.valid && fuse && m->prepare_under_apply) {
         HIP_TRY(hipEventRecord(m->ev_reduced, st));
         HIP_TRY(hipStreamWaitEvent(m->side, m->ev_reduced, 0));
-        if ((rc = enqueue_prepare(m, following))) return rc;
+        if ((rc = enqueue_prepare(m, following, false))) return rc;
     }
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
@@ -1148,6 +1174,7 @@ int tensair_model_destroy(tensair_model *m)
         if (m->ev_segs) (void)hipEventDestroy(m->ev_segs);
         if (m->ev_index) (void)hipEventDestroy(m->ev_index);
         if (m->ev_prep) (void)hipEventDestroy(m->ev_prep);
+        if (m->ev_keys) (void)hipEventDestroy(m->ev_keys);
         if (m->ev_reduced) (void)hipEventDestroy(m->ev_reduced);
         if (m->side) {
             (void)hipStreamSynchronize(m->side);   // a pending prefetch still writes the workspace
