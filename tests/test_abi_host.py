@@ -89,3 +89,11 @@ def test_host_side_argument_checks_of_the_further_entry_points():
     assert L.tensair_sgns_grad(None, None, 1, 0, 0, 0, None, None, None, None, None, None) == B.EINVAL
     assert L.tensair_profile(None, 1) == B.EINVAL
     assert L.tensair_model_destroy(None) == B.OK             # destroying nothing is allowed
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is the one-GPU worker step: bench.py says so and exits instead of pretending to scale."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one-GPU" in r.stderr and r.stdout.strip() == ""
