@@ -28,6 +28,9 @@
  *   - Return value: TENSAIR_OK or a negative tensair_status code; host-detectable
  *     argument errors are reported before anything is launched;
  *     tensair_last_error() gives a thread-local message.
+ *   - A model handle keeps host-side state between calls (announced mini-batches, the order of
+ *     work on the library's stream): calls on one handle must not overlap in time on the host;
+ *     different handles are independent.
  *   - Data errors seen by kernels (a peer gradient whose ids are out of range or not
  *     strictly ascending) never fault: the offending rows are skipped, a device
  *     status word is set, and tensair_status() reports TENSAIR_EDATA.
