@@ -301,6 +301,29 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
  * streaming-bandwidth ceiling of the box and the calibration of its HBM byte counters. */
 int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
 
+/* tensair_dasgd_apply for callers that cannot allocate device memory and hold no model handle: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same update, same
+ * kernels: W[r] <- W[r] - lr * (own[r] + peer_1[r] + ... + peer_K[r]) for every row in the union of the
+ * sources' row ids, fp32 sum in that order, one rounding on store (round-to-nearest-even for bf16).
+ * The tables are passed directly (DEVICE, [vocab][row_stride] of dtype, 16-byte aligned); own may be
+ * NULL; peers: HOST array of n_peers structs.  The index scratch of the update (12.6 MB) is a fixed
+ * device array inside the library instead of a workspace, which limits the call to
+ * vocab <= TENSAIR_STATIC_MAX_VOCAB and n_peers <= TENSAIR_STATIC_MAX_PEERS: larger sizes are refused
+ * with TENSAIR_ECAPACITY before anything is enqueued.  The call allocates nothing (no hipMalloc, no
+ * hipFree, no allocating library routine) and does not wait for the GPU; the device of `stream` must
+ * be the current device.  Every GPU holds one copy of the scratch, shared by all calls on that GPU:
+ * the call clears what it needs itself, and calls that overlap in time on one GPU (two streams, two
+ * threads) race -- keep them on one stream.
+ * status: DEVICE int32 or NULL.  Data errors seen by the kernels (ids out of range or not strictly
+ * ascending, a row count above its capacity) never fault; the offending rows are skipped and the bits
+ * 1 (bad id), 2 (bad order), 4 (overflow) are OR-ed into *status, which the caller clears and reads. */
+#define TENSAIR_STATIC_MAX_VOCAB 2097152 /* 2^21 rows per table */
+#define TENSAIR_STATIC_MAX_PEERS 15
+int tensair_dasgd_apply_static(void *w_in, void *w_out, int64_t vocab, int32_t dim, int32_t row_stride,
+                               int32_t dtype, const tensair_sparse_grad *own,
+                               const tensair_sparse_grad *peers, int32_t n_peers, float lr,
+                               int32_t *status, void *stream);
+
 /* Waits for the library's own stream (a pending prefetch), then frees the host handle. */
 int tensair_model_destroy(tensair_model *m);
 

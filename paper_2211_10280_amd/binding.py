@@ -19,6 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libtensair.so")
 F32, BF16 = 0, 1
 OK, EINVAL, ECAPACITY, EHIP, EDATA = 0, -1, -2, -3, -4
 MAX_PEERS = 31
+STATIC_MAX_VOCAB = 1 << 21
+STATIC_MAX_PEERS = 15
 RESAMPLE_NEGATIVES = 1
 STOCHASTIC_ROUNDING = 2
 
@@ -29,6 +31,7 @@ SYMBOLS = [
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
     "tensair_prefetch", "tensair_grad_add", "tensair_dense_apply", "tensair_lookup",
     "tensair_cosine_difference", "tensair_grad_pack", "tensair_dasgd_apply_packed", "tensair_step_packed",
+    "tensair_dasgd_apply_static",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -111,6 +114,9 @@ def lib():
         L.tensair_step_packed.argtypes = [vp, vp, i64, i64, i32, u32, C.POINTER(SparseGrad), i32, C.c_float,
                                           C.POINTER(SparseGrad), C.POINTER(SparseGrad), vp, vp]
         L.tensair_step_packed.restype = C.c_int
+        L.tensair_dasgd_apply_static.argtypes = [vp, vp, i64, i32, i32, i32, C.POINTER(SparseGrad),
+                                                 C.POINTER(SparseGrad), i32, C.c_float, vp, vp]
+        L.tensair_dasgd_apply_static.restype = C.c_int
         L.tensair_status.argtypes = [vp, vp]
         L.tensair_status.restype = C.c_int
         L.tensair_model_destroy.argtypes = [vp]
@@ -268,6 +274,15 @@ def tensair_dasgd_apply(h, own, peers, lr: float, stream=None):
     arr = _peer_array(peers)
     _check(lib().tensair_dasgd_apply(h, C.byref(own.c) if own is not None else None, arr, len(peers),
                                      C.c_float(lr), _stream(stream)))
+
+
+def tensair_dasgd_apply_static(w_in, w_out, dim: int, own, peers, lr: float, status=None, stream=None):
+    """w_in, w_out: [vocab, row_stride] tables of the same dtype; status: int32 tensor of one element or None."""
+    dt = F32 if w_in.dtype == torch.float32 else BF16
+    arr = _peer_array(peers)
+    _check(lib().tensair_dasgd_apply_static(_ptr(w_in), _ptr(w_out), w_in.shape[0], dim, w_in.shape[1], dt,
+                                            C.byref(own.c) if own is not None else None, arr, len(peers),
+                                            C.c_float(lr), _ptr(status), _stream(stream)))
 
 
 def tensair_step(h, tokens, center_begin: int, n_centers: int, epoch: int, peers, lr: float,

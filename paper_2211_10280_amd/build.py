@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtensair.so")
-SOURCES = ["api.hip", "sample.hip", "sort.hip", "grad.hip", "apply.hip", "dense.hip", "probe.hip"]
+SOURCES = ["api.hip", "sample.hip", "sort.hip", "grad.hip", "apply.hip", "dense.hip", "probe.hip", "noalloc.hip"]
 HEADERS = ["dev_common.h", "kernels.h", os.path.join("..", "..", "include", "tensair.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -18,6 +18,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 int fail(int code, const char *fmt, ...)
 {
     va_list ap;
@@ -89,6 +90,15 @@ Sizes sizes_of(const tensair_config &c)
 }
 
 }  // namespace
+
+int tn_fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
 
 // Everything about a mini-batch that does not depend on the tables: keys (pairs and negatives), their
 // sorted order, segments, unique row ids.  There are two sets, used in turn, so that the set of the

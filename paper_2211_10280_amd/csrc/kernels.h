@@ -208,3 +208,7 @@ void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st);
 
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)
 void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);
+
+// ---- host-side helpers shared by the files that hold C-ABI entry points
+// records the thread-local message of tensair_last_error and returns `code`
+int tn_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));

@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
         pytest.fail("libtensair.so has not been built (python -m paper_2211_10280_amd.build)")
     L = C.CDLL(B.LIB_PATH)
     names = _declared()
-    assert len(names) >= 24
+    assert len(names) >= 25
     for n in names:
         assert hasattr(L, n), n
     assert sorted(B.SYMBOLS) == names        # the binding forwards to exactly these
@@ -81,6 +81,13 @@ def test_host_side_argument_checks_of_the_further_entry_points():
     assert L.tensair_cosine_difference(aligned, aligned, B.F32, 4, 6, 8, aligned, None) == B.EINVAL
     assert L.tensair_cosine_difference(aligned, aligned, B.F32, 4, 8, 4, aligned, None) == B.EINVAL
     assert L.tensair_cosine_difference(aligned, aligned, B.F32, -1, 4, 4, aligned, None) == B.EINVAL
+    # the entry point with the fixed scratch: sizes beyond it are refused first, then the usual checks
+    assert L.tensair_dasgd_apply_static(aligned, aligned, B.STATIC_MAX_VOCAB + 1, 4, 4, B.F32, None, None, 0, 0.1, None, None) == B.ECAPACITY
+    assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 4, 4, B.F32, None, None, B.STATIC_MAX_PEERS + 1, 0.1, None, None) == B.ECAPACITY
+    assert L.tensair_dasgd_apply_static(None, aligned, 64, 4, 4, B.F32, None, None, 0, 0.1, None, None) == B.EINVAL
+    assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 6, 8, B.F32, None, None, 0, 0.1, None, None) == B.EINVAL
+    assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 4, 4, B.F32, None, None, 1, 0.1, None, None) == B.EINVAL
+    assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 4, 4, B.F32, None, None, 0, 0.1, None, None) == B.OK   # nothing to apply
     # calls that need a model
     assert L.tensair_lookup(None, 0, None, 0, None, None) == B.EINVAL
     assert L.tensair_grad_add(None, None, None, None, None) == B.EINVAL
