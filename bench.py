@@ -71,7 +71,7 @@ def main():
     import torch
 
     from paper_2211_10280_amd import binding as B
-    from paper_2211_10280_amd import workload as W
+    import workload as W
     from paper_2211_10280_amd.trainer import DasgdWorker
 
     cfg = W.CONFIGS[args.config]
@@ -260,7 +260,7 @@ def bench_grad_add(args, cfg, tok, counts):
     import torch
 
     from paper_2211_10280_amd import binding as B
-    from paper_2211_10280_amd import workload as W
+    import workload as W
 
     dt = B.F32 if cfg.dtype == "f32" else B.BF16
     m = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch, max(cfg.peers, 1), cfg.seed, counts)
@@ -392,7 +392,7 @@ def bench_streaming(args, cfg, tok, counts):
             oracle.lookup(Wn, odt, D, idn)
             return n / (time.perf_counter() - t0), "the same lookup, once"
     elif args.op == "grad_pack":
-        from paper_2211_10280_amd import workload as W
+        import workload as W
 
         m = B.Model(V, D, B.F32 if cfg.dtype == "f32" else B.BF16, cfg.window, cfg.negatives, cfg.batch, 0, cfg.seed, counts)
         m.w_out.copy_(m.w_in)     # W_out away from zero so that both sides carry non-trivial rows

@@ -3,7 +3,9 @@
 ``tensair_oracle.c`` is the plain sequential statement of the step (double
 arithmetic); this module builds it with gcc and wraps it with ctypes/numpy.
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
-``bench.py`` may import it.  It imports nothing from the product package.
+``bench.py`` may import it.  Nothing under ``oracle/`` imports the product package;
+``oracle/driver.py`` takes its seeded inputs from ``workload.py`` at the repository
+root, which holds none of the method's arithmetic and belongs to neither side.
 
 Paper: TensAIR, arXiv 2211.10280 -- Eq. 1, Algorithm 1 (train), Section 3.1
 (staleness and ordering), Section 4 (sparse updates).

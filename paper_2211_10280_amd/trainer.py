@@ -21,12 +21,13 @@ import numpy as np
 import torch
 
 from . import binding as B
-from . import workload as W
+import workload as W
 
 
 class DasgdWorker:
     def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True,
-                 row_stride=None, bf16_messages=False):
+                 row_stride=None, bf16_messages=False, tables=None):
+        """tables: (w_in, w_out) device tensors of a pre-trained model to train on in place; None: a fresh one."""
         self.cfg = cfg
         self.bf16_messages = bf16_messages
         self.prefetch = prefetch     # announce coming mini-batches with tensair_prefetch
@@ -37,7 +38,7 @@ class DasgdWorker:
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
         self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
                              max(cfg.peers, 0), cfg.seed, counts, worker_id=0, row_stride=row_stride,
-                             device=device, flags=flags)
+                             device=device, flags=flags, tables=tables)
         # a second handle computes the peers' gradients on snapshots (its tables are rebound per call)
         self.peer_model = None
         if cfg.peers > 0:

@@ -12,7 +12,7 @@ from helpers import (BF16_CHAIN_FRAC, BF16_CHAIN_MAX, BF16_MSG_CHAIN_FRAC, BF16_
                      TOL_ROWS, TOL_TABLE, bf16_to_f32, bf16_ulp_err, rel_l2, rows_rel)
 from oracle.driver import OracleWorker
 from paper_2211_10280_amd import binding as B
-from paper_2211_10280_amd import workload as W
+import workload as W
 from paper_2211_10280_amd.trainer import DasgdWorker
 
 pytestmark = pytest.mark.gpu
@@ -388,13 +388,11 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
         e = max(rows_rel(rows_in, og.gin.rows), rows_rel(rows_out, og.gout.rows))
         worst_rows = max(worst_rows, e)
         assert abs(gw.mean_loss.item() - og.loss) <= TOL_LOSS * og.loss, f"step {t}"
-        # peers: ids bit-exact as well (they were computed on the GPU from the GPU's own snapshots)
+        # peers: row ids bit-exact as well (they were computed on the GPU from the GPU's own snapshots)
         peer_side = gw.peer_bufs if cfg.grad_buffer == 1 else [p[0] for p in gw.peer_acc]
         for k, pg in enumerate(grads[1:]):
-            ui, uo = peer_side[k].sizes()
-            assert ui == pg.gin.ids.size and uo == pg.gout.ids.size, f"step {t} peer {k + 1}"
-        if cfg.peers and cfg.max_stale:
-            assert all(s % (cfg.peers + 1) == 0 for s in ow.last_staleness)
+            (pi, _), (po, _) = peer_side[k].to_host()
+            assert np.array_equal(pi, pg.gin.ids) and np.array_equal(po, pg.gout.ids), f"step {t} peer {k + 1}"
         if cfg.grad_buffer > 1 and (t + 1) % cfg.grad_buffer == 0:
             # the buffer this worker broadcasts: the sum of its last grad_buffer gradients
             (bi, br), (bo, bq) = gw.sent.to_host()

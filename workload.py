@@ -4,7 +4,9 @@ This module produces *data only*: token streams, unigram counts, the batch
 schedule (which slice of the stream each worker sees at each step) and the
 staleness draws for peer snapshots.  It contains none of the method's
 arithmetic (no Philox, no alias table, no gradients), so both the HIP path and
-the CPU oracle may be fed from it without sharing any computation.
+the CPU oracle may be fed from it without sharing any computation; it belongs to
+neither (it sits at the repository root, outside the product package and outside
+``oracle/``) and imports neither.
 
 The paper trains its word-embedding model on a 1 % sample of English Wikipedia
 (Section 4, "Sparse vs. Dense Models"); that corpus is not available here, so
