@@ -142,7 +142,10 @@ struct tensair_model {
     float *g, *center_part, *center_loss, *part_out, *part_in, *cross_out, *cross_in;
     int *xinfo_out, *xinfo_in;
     u32 *start[2];
-    u64 *mask[2];
+    u64 *mask[2];              // masks of the update's index, per table (buffer 0)
+    u64 *mask_alt[2];          // a second set (buffer 1): inside tensair_step the two are used in turn, so that
+                               // the one the next step will index can be cleared while this step still reads its own
+    bool mask_clean[2] = {false, false};   // buffer b is all zeros (or will be when everything enqueued so far has run)
     u32 *wbase[2], *wblk[2];   // tensair_grad_add: place of every 64-row word in the summed gradient
     std::vector<uint32_t> h_thr;
     std::vector<int32_t> h_alias;
@@ -150,7 +153,7 @@ struct tensair_model {
     // on next to the caller's stream (the forward pass beside the sort, the index of the coming table
     // update beside the reductions, the preparation of announced mini-batches)
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_fwd = nullptr, ev_segs = nullptr, ev_index = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_fwd = nullptr;
     // mini-batch sets: `busy` is the one the most recent gradient call reads; announced mini-batches are
     // prepared into the other one on the second stream (ev_prep recorded behind them)
     int busy = 1;
@@ -165,12 +168,13 @@ struct tensair_model {
     bool side_follows = false;     // the second stream has waited for the start of the latest gradient call
     // every event recorded on the second stream takes a ticket; the caller's stream is behind all of
     // them up to main_ticket, so a prepared set with prep_ticket <= main_ticket needs no wait
-    u64 side_ticket = 0, main_ticket = 0, prep_ticket = 0, index_ticket = 0, keys_ticket = 0;
-    // set by tensair_step: the index of the coming apply is built on the second stream, next to
-    // the reductions, as soon as the own row ids exist
-    const ApplyArgs *fused_apply = nullptr;
+    u64 side_ticket = 0, main_ticket = 0, prep_ticket = 0, keys_ticket = 0;
+    // set by tensair_step: the index of the coming apply is built by extra workgroups at the front of the
+    // forward pass (clearing) and of the segmented reduction (the id lists), on the caller's stream
+    ApplyArgs *fused_apply = nullptr;
     bool fused_index_done = false;
     bool prepare_under_apply = false;   // tensair_step: the table update is long enough to hide a preparation
+    Prefetched deferred;                // the mini-batch to prepare under that update (enqueued by tensair_step)
     u32 apply_serial = 0;               // table updates enqueued so far (stochastic rounding draws from it)
     // stage timing (tensair_profile): events recorded on the caller's stream
     int prof_level = 0;
@@ -232,6 +236,7 @@ size_t carve(const tensair_config &c, const Sizes &s, char *base, tensair_model 
     for (int t = 0; t < 2; ++t) {
         p = take((size_t)(s.words + 1) * K1 * 4); if (m) m->start[t] = (u32 *)p;
         p = take((size_t)s.words * K1 * 8); if (m) m->mask[t] = (u64 *)p;
+        p = take((size_t)s.words * K1 * 8); if (m) m->mask_alt[t] = (u64 *)p;
         p = take((size_t)s.words * 4); if (m) m->wbase[t] = (u32 *)p;
         p = take((size_t)(s.words / TN_UNION_WORDS + 1) * 4); if (m) m->wblk[t] = (u32 *)p;
     }
@@ -286,22 +291,26 @@ enum { PF_BEGIN_GRAD = 0, PF_KEYS, PF_FORWARD, PF_SORT, PF_SEGMENTS, PF_REDUCE_I
        PF_BEGIN_APPLY, PF_APPLY_INDEX, PF_APPLY_UPDATE, PF_BEGIN_ADD, PF_ADD_INDEX, PF_ADD_ROWS,
        PF_BEGIN_PACK, PF_PACK };
 
-void mark(tensair_model *m, int tag, hipStream_t st)
+// records a timing event on `st` if stage timing asks for this tag; returns it (another stream may wait on
+// it, which saves that stream's fork an event of its own) or nullptr
+hipEvent_t mark(tensair_model *m, int tag, hipStream_t st)
 {
-    if (m->prof_level == 0) return;
+    if (m->prof_level == 0) return nullptr;
     if (m->prof_level == 1 && tag != PF_APPLY_INDEX && tag != PF_APPLY_UPDATE && tag != PF_ADD_INDEX &&
         tag != PF_ADD_ROWS && tag != PF_BEGIN_PACK && tag != PF_PACK)
-        return;
-    if (m->prof_marks.size() >= 65536) return;
+        return nullptr;
+    if (m->prof_marks.size() >= 65536) return nullptr;
     hipEvent_t ev;
     if (m->prof_used < m->prof_pool.size()) {
         ev = m->prof_pool[m->prof_used];
     } else {
-        if (hipEventCreate(&ev) != hipSuccess) return;
+        if (hipEventCreate(&ev) != hipSuccess) return nullptr;
         m->prof_pool.push_back(ev);
     }
     ++m->prof_used;
-    if (hipEventRecord(ev, st) == hipSuccess) m->prof_marks.emplace_back(tag, ev);
+    if (hipEventRecord(ev, st) != hipSuccess) return nullptr;
+    m->prof_marks.emplace_back(tag, ev);
+    return ev;
 }
 
 i64 pair_count(const tensair_config &c, i64 T, i64 begin, int n)
@@ -408,8 +417,6 @@ int tensair_model_init(tensair_model **out, const tensair_config *cfg, void *w_i
     if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_fwd, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&m->ev_segs, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&m->ev_index, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_prep, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_keys, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->ev_reduced, hipEventDisableTiming) != hipSuccess) {
@@ -584,6 +591,22 @@ static int enqueue_prepare(tensair_model *m, const Prefetched &d, bool late)
     return TENSAIR_OK;
 }
 
+// After a HIP call has failed in the middle of a call that had already forked work to the second stream, the
+// two streams and the host's record of them may disagree.  Wait for the second stream (best effort), forget
+// every announcement and count the caller's stream as behind everything, so that the next call on the handle
+// starts from a known state instead of racing leftover work.
+static void abandon_side_work(tensair_model *m)
+{
+    if (m->side) (void)hipStreamSynchronize(m->side);
+    m->pend.valid = m->next.valid = m->deferred.valid = false;
+    m->pend_late = false;
+    m->side_follows = false;
+    m->main_ticket = m->side_ticket;
+    m->fused_apply = nullptr;
+    m->fused_index_done = false;
+    m->mask_clean[0] = m->mask_clean[1] = false;
+}
+
 int tensair_prefetch(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
                      int32_t n_centers, uint32_t epoch, void *stream)
 {
@@ -614,12 +637,14 @@ int tensair_prefetch(tensair_model *m, const int32_t *tokens, int64_t n_tokens, 
         HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
         m->side_follows = true;
     }
-    return enqueue_prepare(m, d, true);
+    const int rc2 = enqueue_prepare(m, d, true);
+    if (rc2 == TENSAIR_EHIP) abandon_side_work(m);
+    return rc2;
 }
 
-int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
-                      int32_t n_centers, uint32_t epoch, tensair_sparse_grad *grad_out, float *mean_loss,
-                      int32_t *negatives_dbg, int32_t *seg_offsets_in, int32_t *seg_offsets_out, void *stream)
+static int sgns_grad_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                          int32_t n_centers, uint32_t epoch, tensair_sparse_grad *grad_out, float *mean_loss,
+                          int32_t *negatives_dbg, int32_t *seg_offsets_in, int32_t *seg_offsets_out, void *stream)
 {
     if (!m || !grad_out) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     const tensair_config &c = m->cfg;
@@ -645,9 +670,12 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     // segments, reductions) stays on the caller's stream, so that none of its links is a cross-stream
     // wait, and the forward pass runs next to the sort on the library's second stream.  With a matching
     // prefetch the keys, the sorted order and the segments are already there (made on the second stream
-    // while the previous step ran) and the caller's stream starts with the forward pass.  Either way,
-    // inside tensair_step the second stream builds the index of the coming apply meanwhile.  When every
-    // stage is being timed (profile level 2) everything is serialised on the caller's stream.
+    // while the previous step ran) and the caller's stream starts with the forward pass.  The small jobs
+    // around them -- the prepared row index to the caller's buffers, and inside tensair_step the index of
+    // the coming table update -- ride at the front of the forward and the reduction launches: every event
+    // between streams idles the waiting stream for microseconds, and a launch of their own is not worth
+    // one.  When every stage is being timed (profile level 2) everything is serialised on the caller's
+    // stream in launches of its own.
     const bool overlap = m->prof_level < 2;
     const bool fuse = overlap && m->fused_apply != nullptr;
     const bool prepared = overlap && negatives_dbg == nullptr &&
@@ -657,6 +685,7 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     // call does not follow are dropped
     const Prefetched following = prepared ? m->next : Prefetched();
     m->next.valid = false;
+    m->deferred.valid = false;
     // this call takes the set that announced mini-batches are prepared into; one that does not match
     // is overwritten, after its preparation has finished
     const int u = 1 - m->busy;
@@ -692,32 +721,73 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     f.center_loss = mean_loss ? m->center_loss : nullptr;   // loss terms only on request
     f.inv_P = 1.0f / (float)P;
 
+    AuxWork aux_fwd, aux_red;     // what rides at the front of the forward pass / of the reduction
+    tn_aux_none(aux_fwd);
+    tn_aux_none(aux_red);
+    if (fuse) {
+        // The index of the coming table update.  Its masks must be zero before the id lists are indexed, and the
+        // two cannot share a launch, so there are two sets of masks: this step indexes a clean one, with the
+        // forward pass (hidden behind its row gathers) where the id lists are known by then -- the peers'
+        // always, the own one if the mini-batch was prepared -- else with the reductions; the other set, which
+        // the previous step used, is cleared with the reductions and is the clean one of the next step.
+        ApplyArgs &fa = *m->fused_apply;
+        int pick = m->mask_clean[0] ? 0 : (m->mask_clean[1] ? 1 : -1);
+        if (pick < 0) {           // the first step, or other calls have used both sets since
+            pick = 0;
+            ApplyArgs full = fa;  // the whole buffer, whatever layout its last user had
+            full.n_src = (c.max_peers + 1 > 2 ? c.max_peers + 1 : 2);
+            tn_launch_apply_clear(full, st);
+        }
+        for (int t = 0; t < 2; ++t) fa.mask[t] = pick ? m->mask_alt[t] : m->mask[t];
+        m->mask_clean[pick] = false;
+        const bool own_early = prepared && !split;   // the own id lists exist when the forward pass starts
+        tn_aux_add_index(aux_fwd, fa, own_early ? 0 : 1, fa.n_src);
+        if (!own_early) tn_aux_add_index(aux_red, fa, 0, 1);
+        if (!m->mask_clean[1 - pick]) {
+            const size_t all = (size_t)s.words * (size_t)(c.max_peers + 1 > 2 ? c.max_peers + 1 : 2);
+            tn_aux_add_clear(aux_red, pick ? m->mask[0] : m->mask_alt[0], pick ? m->mask[1] : m->mask_alt[1], all);
+            m->mask_clean[1 - pick] = true;
+        }
+        m->fused_index_done = true;
+    }
+
     if (prepared) {
-        // second stream: this mini-batch's row index to the caller's buffers and the index of the coming
-        // apply, then the preparation of the following mini-batch
-        HIP_TRY(hipEventRecord(m->ev_fork, st));
-        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
-        m->side_follows = true;
+        // this mini-batch's row index goes to the caller's buffers with the forward pass -- with the
+        // reductions if the forward pass starts on the keys alone, before the sort has finished
         RowIndexCopy rc2;
         rc2.side[0] = {S.ids_in, S.n_rows, S.off_in, grad_out->in.row_ids, grad_out->in.n_rows, seg_offsets_in};
         rc2.side[1] = {S.ids_out, S.n_rows + 1, S.off_out, grad_out->out.row_ids, grad_out->out.n_rows,
                        seg_offsets_out};
-        tn_launch_copy_row_index(rc2, tensair_capacity_out(&c, n_centers), m->side);
-        if (fuse) {
-            tn_launch_apply_clear(*m->fused_apply, m->side);
-            tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
-            m->fused_index_done = true;
+        tn_aux_add_copy(split ? aux_red : aux_fwd, rc2, tensair_capacity_out(&c, n_centers));
+        if (fuse) {   // the own id lists are indexed where they are, whichever launch copies them
+            AuxWork &ix = split ? aux_red : aux_fwd;
+            ApplySrc &o_in = ix.apply.src[0][0], &o_out = ix.apply.src[1][0];
+            o_in.ids = S.ids_in;
+            o_in.n_rows = S.n_rows;
+            o_in.capacity = tensair_capacity_in(&c, c.max_centers);
+            o_out.ids = S.ids_out;
+            o_out.n_rows = S.n_rows + 1;
+            o_out.capacity = tensair_capacity_out(&c, c.max_centers);
         }
-        HIP_TRY(hipEventRecord(m->ev_index, m->side));
-        m->index_ticket = ++m->side_ticket;
-        // caller's stream: forward pass on the prepared keys
-        tn_launch_forward(f, st);
+        // Where a long table update follows (tensair_step decides), the following mini-batch is prepared
+        // under that update, which is bound by HBM bandwidth and loses little to it; otherwise next to this
+        // call's forward pass, for which the second stream gets behind the caller's stream here.
+        const bool under_apply = fuse && m->prepare_under_apply;
+        if (following.valid && !under_apply) {
+            HIP_TRY(hipEventRecord(m->ev_fork, st));
+            HIP_TRY(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+            m->side_follows = true;
+        }
+        tn_launch_forward(f, &aux_fwd, st);
         if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, st);
         if (split) {   // the sorted order and the segments of this mini-batch
             HIP_TRY(hipStreamWaitEvent(st, m->ev_prep, 0));
             if (consumed_prep_ticket > m->main_ticket) m->main_ticket = consumed_prep_ticket;
         }
-        if (following.valid && !(fuse && m->prepare_under_apply) && (rc = enqueue_prepare(m, following, true))) return rc;
+        if (following.valid) {
+            if (under_apply) m->deferred = following;
+            else if ((rc = enqueue_prepare(m, following, true))) return rc;
+        }
     } else {
         // 1. keys
         enqueue_keys(m, S, w, negatives_dbg, st);
@@ -731,27 +801,22 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
         }
         // 2. forward on the unsorted keys (the sort never writes their buffer): g per occurrence,
         //    per-center share of the W_in gradient, loss terms
-        tn_launch_forward(f, s_fwd);
+        tn_launch_forward(f, &aux_fwd, s_fwd);
         if (mean_loss) tn_launch_loss(m->center_loss, n_centers, f.inv_P, mean_loss, s_fwd);
         mark(m, PF_FORWARD, st);
         if (overlap) {
             HIP_TRY(hipEventRecord(m->ev_fwd, m->side));
-            if (fuse) tn_launch_apply_clear(*m->fused_apply, m->side);
+            ++m->side_ticket;
         }
         // 3./4. sort and segments, row index straight into the caller's buffers
         const RowIndexDst in = {grad_out->in.row_ids, grad_out->in.n_rows, seg_offsets_in, grad_out->in.capacity};
         const RowIndexDst out = {grad_out->out.row_ids, grad_out->out.n_rows, seg_offsets_out,
                                  grad_out->out.capacity};
         enqueue_sort_segments(m, S, w, in, out, st, st);
-        if (fuse) {   // off the critical path: the reductions run meanwhile, the apply waits for ev_index
-            HIP_TRY(hipEventRecord(m->ev_segs, st));
-            HIP_TRY(hipStreamWaitEvent(m->side, m->ev_segs, 0));
-            tn_launch_apply_index(*m->fused_apply, 0, m->fused_apply->n_src, m->side);
-            HIP_TRY(hipEventRecord(m->ev_index, m->side));
-            m->index_ticket = ++m->side_ticket;
-            m->fused_index_done = true;
+        if (overlap) {
+            HIP_TRY(hipStreamWaitEvent(st, m->ev_fwd, 0));
+            m->main_ticket = m->side_ticket;
         }
-        if (overlap) HIP_TRY(hipStreamWaitEvent(st, m->ev_fwd, 0));
     }
 
     // 5. segmented reductions: duplicates of a row summed in sorted (= occurrence) order
@@ -790,28 +855,43 @@ int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens,
     r_out.dtype = c.dtype;
     r_out.stride = c.row_stride;
     if (overlap) {   // both sides in one launch
-        tn_launch_segreduce(&r_out, &r_in, st);
+        tn_launch_segreduce(&r_out, &r_in, &aux_red, st);
     } else {         // one after the other, so that each can be timed
-        tn_launch_segreduce(nullptr, &r_in, st);
+        tn_launch_segreduce(nullptr, &r_in, nullptr, st);
         mark(m, PF_REDUCE_IN, st);
-        tn_launch_segreduce(&r_out, nullptr, st);
+        tn_launch_segreduce(&r_out, nullptr, nullptr, st);
     }
     mark(m, PF_REDUCE_OUT, st);
-    // the row index copied on the second stream belongs to this call's results
-    if (prepared && !fuse) {
-        HIP_TRY(hipStreamWaitEvent(st, m->ev_index, 0));
-        m->main_ticket = m->index_ticket;
-    }
-    // Where a long table update follows (tensair_step decides), the following mini-batch is prepared
-    // behind this call's reductions: next to them it would slow them down, next to the update, which is
-    // bound by HBM bandwidth, it costs little.  Otherwise it was enqueued above, next to the forward pass.
-    if (following.valid && fuse && m->prepare_under_apply) {
-        HIP_TRY(hipEventRecord(m->ev_reduced, st));
-        HIP_TRY(hipStreamWaitEvent(m->side, m->ev_reduced, 0));
-        if ((rc = enqueue_prepare(m, following, false))) return rc;
-    }
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
+}
+
+int tensair_sgns_grad(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
+                      int32_t n_centers, uint32_t epoch, tensair_sparse_grad *grad_out, float *mean_loss,
+                      int32_t *negatives_dbg, int32_t *seg_offsets_in, int32_t *seg_offsets_out, void *stream)
+{
+    const int rc = sgns_grad_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, grad_out, mean_loss,
+                                  negatives_dbg, seg_offsets_in, seg_offsets_out, stream);
+    if (rc == TENSAIR_EHIP && m) abandon_side_work(m);
+    return rc;
+}
+
+// The preparation of the mini-batch that tensair_sgns_grad left in m->deferred: enqueued on the second
+// stream behind everything that is on the caller's stream now (the reductions), so that it runs under the
+// table update that the caller enqueues next.  `ev`: an event just recorded on the caller's stream, or
+// nullptr to record one.
+static int enqueue_deferred_prepare(tensair_model *m, hipEvent_t ev, hipStream_t st)
+{
+    if (!m->deferred.valid) return TENSAIR_OK;
+    const Prefetched d = m->deferred;
+    m->deferred.valid = false;
+    if (!ev) {
+        HIP_TRY(hipEventRecord(m->ev_reduced, st));
+        ev = m->ev_reduced;
+    }
+    HIP_TRY(hipStreamWaitEvent(m->side, ev, 0));
+    m->side_follows = true;
+    return enqueue_prepare(m, d, false);
 }
 
 // peers are fp32 gradients (`peers`) or bfloat16 messages (`packed`), never both
@@ -860,6 +940,7 @@ static int apply_impl(tensair_model *m, const tensair_sparse_grad *own, const te
     if (!own && n_peers == 0) return TENSAIR_OK;
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_APPLY, st);
+    m->mask_clean[0] = false;
     tn_launch_apply_clear(a, st);
     tn_launch_apply_index(a, 0, a.n_src, st);
     mark(m, PF_APPLY_INDEX, st);
@@ -957,6 +1038,7 @@ int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensa
     }
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_ADD, st);
+    m->mask_clean[0] = false;
     tn_launch_grad_sum_index(g, st);
     mark(m, PF_ADD_INDEX, st);
     tn_launch_grad_sum_rows(g, st);
@@ -997,6 +1079,7 @@ static int step_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, 
     }
     m->fused_apply = &a;
     m->fused_index_done = false;
+    m->deferred.valid = false;
     {   // rough times of the table update (bytes of the gradient blocks at their largest, at 5 TB/s) and of
         // the preparation of a mini-batch (0.2 ns per occurrence plus its launches)
         const tensair_config &c = m->cfg;
@@ -1007,20 +1090,20 @@ static int step_impl(tensair_model *m, const int32_t *tokens, int64_t n_tokens, 
         const double t_prepare = occ * 0.2e-9 + 60e-6;
         m->prepare_under_apply = t_apply >= 2.0 * t_prepare;
     }
-    rc = tensair_sgns_grad(m, tokens, n_tokens, center_begin, n_centers, epoch, own_out, mean_loss, nullptr,
-                           nullptr, nullptr, stream);
+    rc = sgns_grad_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, own_out, mean_loss, nullptr,
+                        nullptr, nullptr, stream);
     m->fused_apply = nullptr;
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     mark(m, PF_BEGIN_APPLY, st);
-    if (m->fused_index_done) {
-        HIP_TRY(hipStreamWaitEvent(st, m->ev_index, 0));
-        m->main_ticket = m->index_ticket;
-    } else {
+    if (!m->fused_index_done) {   // an empty mini-batch, or every stage in a launch of its own
+        m->mask_clean[0] = false;
         tn_launch_apply_clear(a, st);
         tn_launch_apply_index(a, 0, a.n_src, st);
     }
-    mark(m, PF_APPLY_INDEX, st);
+    // the event that opens the timing of the table update also lets the second stream go
+    const hipEvent_t ev = mark(m, PF_APPLY_INDEX, st);
+    if ((rc = enqueue_deferred_prepare(m, ev, st))) return rc;
     tn_launch_apply_update(a, st);
     ++m->apply_serial;
     mark(m, PF_APPLY_UPDATE, st);
@@ -1032,8 +1115,10 @@ int tensair_step(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int6
                  int32_t n_centers, uint32_t epoch, const tensair_sparse_grad *peers, int32_t n_peers,
                  float lr, tensair_sparse_grad *own_out, float *mean_loss, void *stream)
 {
-    return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, peers, nullptr, n_peers, lr, own_out,
-                     nullptr, mean_loss, stream);
+    const int rc = step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, peers, nullptr, n_peers, lr,
+                             own_out, nullptr, mean_loss, stream);
+    if (rc == TENSAIR_EHIP && m) abandon_side_work(m);
+    return rc;
 }
 
 int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_tokens, int64_t center_begin,
@@ -1042,8 +1127,10 @@ int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_token
                         void *stream)
 {
     if (n_peers > 0 && !peers) return fail(TENSAIR_EINVAL, "peers is NULL");
-    return step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, nullptr, peers, n_peers, lr, own_out,
-                     own_msg_out, mean_loss, stream);
+    const int rc = step_impl(m, tokens, n_tokens, center_begin, n_centers, epoch, nullptr, peers, n_peers, lr,
+                             own_out, own_msg_out, mean_loss, stream);
+    if (rc == TENSAIR_EHIP && m) abandon_side_work(m);
+    return rc;
 }
 
 int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,
@@ -1181,8 +1268,6 @@ int tensair_model_destroy(tensair_model *m)
         for (hipEvent_t ev : m->prof_pool) (void)hipEventDestroy(ev);
         if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
         if (m->ev_fwd) (void)hipEventDestroy(m->ev_fwd);
-        if (m->ev_segs) (void)hipEventDestroy(m->ev_segs);
-        if (m->ev_index) (void)hipEventDestroy(m->ev_index);
         if (m->ev_prep) (void)hipEventDestroy(m->ev_prep);
         if (m->ev_keys) (void)hipEventDestroy(m->ev_keys);
         if (m->ev_reduced) (void)hipEventDestroy(m->ev_reduced);

@@ -22,8 +22,11 @@
 // peer block with holes, lose 20 % of the bandwidth between them, and the gradient calculation is
 // itself bound by memory traffic, so nothing was gained by the overlap.
 
+#include <string.h>
+
 #include <type_traits>
 
+#include "aux_dev.h"
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -32,73 +35,16 @@
 #endif
 
 // ---------------------------------------------------------------- index
+// (the work itself is in aux_dev.h: inside tensair_step it rides at the front of other launches)
 __global__ void __launch_bounds__(BLOCK) k_apply_clear(u64 *m0, u64 *m1, size_t n)
 {
-    size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x;
-    if (i < n) {
-        m0[i] = 0ull;
-        m1[i] = 0ull;
-    }
+    aux_clear_masks(m0, m1, n, (int)blockIdx.x);
 }
 
 // grid: (blocks, sources, 2 tables); every wave takes 64 consecutive ids of source k0 + blockIdx.y.
 __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 {
-    const int k = k0 + blockIdx.y, tb = blockIdx.z;
-    const ApplySrc &s = a.src[tb][k];
-    if (s.ids == nullptr) return;
-    int U = *s.n_rows;
-    if (U < 0) U = 0;
-    if ((i64)U > s.capacity) {
-        U = (int)s.capacity;
-        if (threadIdx.x == 0 && blockIdx.x == 0) atomicOr(a.status, ST_OVERFLOW);
-    }
-    const int ns = a.n_src;
-    u32 *start = a.start[tb];
-    u64 *mask = a.mask[tb];
-    const int lane = lane_id();
-    const int V = (int)a.V;
-    // wave-uniform trip count: every lane takes part in the shuffles
-    for (int base = (blockIdx.x * WAVES_PER_BLOCK + uniform((int)(threadIdx.x >> 6))) * WAVE; base < U;
-         base += gridDim.x * BLOCK) {
-        const int i = base + lane;
-        const bool valid = i < U;
-        int id = valid ? s.ids[i] : 0;
-        int prev = (valid && i > 0) ? s.ids[i - 1] : -1;
-        int next = (i + 1 < U) ? s.ids[i + 1] : -1;
-        if (valid) {
-            if ((u32)id >= (u32)V) {
-                atomicOr(a.status, ST_BAD_ID);
-                id = V - 1;
-            }
-            if (id <= prev) atomicOr(a.status, ST_BAD_ORDER);
-        }
-        if ((u32)prev >= (u32)V) prev = (prev < 0) ? -64 : V - 1;
-        if ((u32)next >= (u32)V) next = (next < 0) ? -64 : V - 1;
-        const int w = valid ? (id >> 6) : -2 - lane;          // invalid lanes: unique keys
-        const bool head = valid && ((prev >> 6) != w);        // first id of its word
-        if (head) start[(size_t)w * ns + k] = (u32)i;
-        // segmented inclusive OR over lanes with equal w (equal keys are contiguous)
-        u64 m = valid ? (1ull << (id & 63)) : 0ull;
-#pragma unroll
-        for (int o = 1; o < WAVE; o <<= 1) {
-            u64 m2 = (u64)__shfl_up((unsigned long long)m, o, WAVE);
-            int w2 = __shfl_up(w, o, WAVE);
-            if (lane >= o && w2 == w) m |= m2;
-        }
-        const int w_dn = __shfl_down(w, 1, WAVE);
-        const bool tail = valid && (lane == WAVE - 1 || w_dn != w);   // last lane of its run
-        const int w0 = __shfl(w, 0, WAVE);
-        const int head0 = __shfl((int)head, 0, WAVE);
-        if (tail) {
-            const bool open_left = (w == w0) && !head0;               // run began in an earlier wave
-            const bool open_right = (lane == WAVE - 1) && ((next >> 6) == w);
-            if (open_left || open_right)
-                atomicOr((unsigned long long *)&mask[(size_t)w * ns + k], (unsigned long long)m);
-            else
-                mask[(size_t)w * ns + k] = m;
-        }
-    }
+    aux_index_source(a, k0 + (int)blockIdx.y, (int)blockIdx.z, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // ---------------------------------------------------------------- apply
@@ -245,8 +191,8 @@ k_apply(ApplyArgs a, int nblocks)
         if (k < ns) {
             const ApplySrc &s = a.src[tb][k];
             if (s.ids != nullptr) {
-                u64 mk = a.mask[tb][(size_t)word * ns + k];
-                st = a.start[tb][(size_t)word * ns + k];
+                u64 mk = a.mask[tb][idx_at(words, k, word)];
+                st = a.start[tb][idx_at(words, k, word)];
                 const int lo = sub * G;
                 st += (u32)__popcll(mk & ((1ull << lo) - 1ull));
                 m = (G == 64) ? mk : ((mk >> lo) & ((1ull << (G & 63)) - 1ull));
@@ -315,6 +261,55 @@ static void launch_apply_p(const ApplyArgs &a, hipStream_t st)
     else launch_apply_t<T, STREAM, false>(a, st);
 }
 
+static int index_blocks_for(const ApplyArgs &a, int k_begin, int k_end)
+{
+    // enough waves to cover the largest possible id list, grid-strided
+    i64 maxcap = 1;
+    for (int tb = 0; tb < 2; ++tb)
+        for (int k = k_begin; k < k_end; ++k)
+            if (a.src[tb][k].ids && a.src[tb][k].capacity > maxcap) maxcap = a.src[tb][k].capacity;
+    i64 want = (maxcap + BLOCK * AUX_INDEX_UNROLL - 1) / (BLOCK * AUX_INDEX_UNROLL);
+    return (int)(want > 2048 ? 2048 : want);
+}
+
+#ifndef AUX_COPY_BLOCKS
+#define AUX_COPY_BLOCKS 32
+#endif
+#ifndef AUX_INDEX_BLOCKS
+#define AUX_INDEX_BLOCKS 256
+#endif
+void tn_aux_none(AuxWork &x) { memset(&x, 0, sizeof(x)); }
+
+void tn_aux_add_clear(AuxWork &x, u64 *mask_in, u64 *mask_out, size_t n)
+{
+    x.clear_mask[0] = mask_in;
+    x.clear_mask[1] = mask_out;
+    x.clear_n = n;
+    x.clear_blocks = (int)((x.clear_n + BLOCK - 1) / BLOCK);
+    x.total = x.clear_blocks + 2 * x.copy_blocks + 2 * (x.k_end - x.k_begin) * x.index_blocks;
+}
+
+void tn_aux_add_copy(AuxWork &x, const RowIndexCopy &c, i64 max_rows)
+{
+    x.copy = c;
+    i64 want = (max_rows + 1 + BLOCK - 1) / BLOCK;
+    x.copy_blocks = (int)(want > AUX_COPY_BLOCKS ? AUX_COPY_BLOCKS : want);
+    x.total = x.clear_blocks + 2 * x.copy_blocks + 2 * (x.k_end - x.k_begin) * x.index_blocks;
+}
+
+void tn_aux_add_index(AuxWork &x, const ApplyArgs &a, int k_begin, int k_end)
+{
+    if (k_end <= k_begin) return;
+    x.apply = a;
+    x.k_begin = k_begin;
+    x.k_end = k_end;
+    // few workgroups per id list, each striding over it: riding in front of another kernel's grid, every
+    // workgroup that finds nothing to do still delays that kernel's own
+    x.index_blocks = index_blocks_for(a, k_begin, k_end);
+    if (x.index_blocks > AUX_INDEX_BLOCKS) x.index_blocks = AUX_INDEX_BLOCKS;
+    x.total = x.clear_blocks + 2 * x.copy_blocks + 2 * (x.k_end - x.k_begin) * x.index_blocks;
+}
+
 void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st)
 {
     const size_t words = (size_t)((a.V + 63) >> 6);
@@ -327,13 +322,7 @@ void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st)
 void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st)
 {
     if (k_end <= k_begin) return;
-    // enough waves to cover the largest possible id list, grid-strided
-    i64 maxcap = 1;
-    for (int tb = 0; tb < 2; ++tb)
-        for (int k = k_begin; k < k_end; ++k)
-            if (a.src[tb][k].ids && a.src[tb][k].capacity > maxcap) maxcap = a.src[tb][k].capacity;
-    i64 want = (maxcap + BLOCK - 1) / BLOCK;
-    int blocks = (int)(want > 2048 ? 2048 : want);
+    const int blocks = index_blocks_for(a, k_begin, k_end);
     hipLaunchKernelGGL(k_apply_index, dim3(blocks, k_end - k_begin, 2), dim3(BLOCK), 0, st, a, k_begin);
 }
 
@@ -358,10 +347,10 @@ void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st)
 // 64-row word its place in the output, so ids come out ascending without any sort or merge.
 #define UNION_WPT (TN_UNION_WORDS / BLOCK)
 
-__device__ __forceinline__ u64 united_mask(const u64 *mask, size_t word, int ns)
+__device__ __forceinline__ u64 united_mask(const u64 *mask, size_t words, size_t word, int ns)
 {
     u64 u = 0;
-    for (int k = 0; k < ns; ++k) u |= mask[word * ns + k];
+    for (int k = 0; k < ns; ++k) u |= mask[idx_at((i64)words, k, (i64)word)];
     return u;
 }
 
@@ -393,7 +382,7 @@ __global__ void __launch_bounds__(BLOCK) k_union_count(GradSumArgs g)
     int cnt = 0;
 #pragma unroll
     for (int j = 0; j < UNION_WPT; ++j)
-        if (w0 + j < words) cnt += __popcll(united_mask(g.a.mask[tb], w0 + j, ns));
+        if (w0 + j < words) cnt += __popcll(united_mask(g.a.mask[tb], words, w0 + j, ns));
     int total;
     block_scan1(cnt, total, sm);
     if (threadIdx.x == 0) g.wblk[tb][blockIdx.x] = (u32)total;
@@ -414,7 +403,7 @@ __global__ void __launch_bounds__(BLOCK) k_union_offsets(GradSumArgs g)
     int cnt = 0;
 #pragma unroll
     for (int j = 0; j < UNION_WPT; ++j) {
-        c[j] = (w0 + j < words) ? __popcll(united_mask(g.a.mask[tb], w0 + j, ns)) : 0;
+        c[j] = (w0 + j < words) ? __popcll(united_mask(g.a.mask[tb], words, w0 + j, ns)) : 0;
         cnt += c[j];
     }
     int total;
@@ -458,8 +447,8 @@ __global__ void __launch_bounds__(BLOCK) k_grad_sum(GradSumArgs g, int nblocks)
         if (k < ns) {
             const ApplySrc &s = a.src[tb][k];
             if (s.ids != nullptr) {
-                mk = a.mask[tb][(size_t)word * ns + k];
-                st = a.start[tb][(size_t)word * ns + k];
+                mk = a.mask[tb][idx_at(words, k, word)];
+                st = a.start[tb][idx_at(words, k, word)];
                 U = *s.n_rows;
                 if ((i64)U > s.capacity) U = (int)s.capacity;
                 rows_ptr = (u64)s.rows;

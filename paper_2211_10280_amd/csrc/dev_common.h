@@ -290,6 +290,10 @@ __device__ __forceinline__ philox_out philox4x32_10(u32 c0, u32 c1, u32 c2, u32 
     return philox_out{c0, c1, c2, c3};
 }
 
+// ---------------------------------------------------------------- index of the table update
+// start[] and mask[] hold one entry per (source, 64-row word of the vocabulary), source by source
+__host__ __device__ __forceinline__ size_t idx_at(i64 words, int k, i64 word) { return (size_t)k * (size_t)words + (size_t)word; }
+
 // ---------------------------------------------------------------- pair arithmetic
 // Number of (center, context) pairs of the positions [0, p) in a stream of T tokens with
 // window w: position x has min(x, w) contexts on the left and min(T-1-x, w) on the right.

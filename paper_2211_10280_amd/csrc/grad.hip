@@ -14,6 +14,7 @@
 //             is therefore independent of how hot a row is.
 #include <string.h>
 
+#include "aux_dev.h"
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -165,13 +166,20 @@ struct SegShape {
 
 // LOSS: also accumulate the loss terms (only when the caller asked for the mean loss).
 template <typename T, int NQ, bool TAIL, bool LOSS>
-__global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
+__global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a, AuxWork aux)
 {
     typedef WaveRow<NQ, TAIL> Row;
     constexpr int UNROLL = FwdShape<T, NQ, TAIL>::unroll;
     __shared__ float red[WAVES_PER_BLOCK][(NQ * 4 + (TAIL ? 1 : 0)) * WAVE];
     __shared__ float lred[WAVES_PER_BLOCK];
-    const int i = blockIdx.x;
+    // the first aux.total workgroups carry the small jobs that ride with this launch (measured: spread among
+    // the centers' workgroups instead, alternating one by one or in runs of eight, they cost the forward pass
+    // 25 to 35 us more than in front of it)
+    if ((int)blockIdx.x < aux.total) {
+        aux_block(aux, (int)blockIdx.x);
+        return;
+    }
+    const int i = (int)blockIdx.x - aux.total;
     const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
     const BatchDesc &b = a.b;
     const i64 p = b.begin + i;
@@ -252,33 +260,38 @@ __global__ void __launch_bounds__(BLOCK) k_forward(FwdArgs a)
 }
 
 template <typename T, bool LOSS>
-static void launch_forward_t(const FwdArgs &a, hipStream_t st)
+static void launch_forward_t(const FwdArgs &a, const AuxWork &aux, hipStream_t st)
 {
     const int full = a.D / (4 * WAVE);           // float4 registers that every lane uses
     const int rest = a.D - full * 4 * WAVE;      // elements beyond them
-    dim3 grid(a.b.n_centers), blk(BLOCK);
+    dim3 grid(aux.total + a.b.n_centers), blk(BLOCK);
     if (rest > 0 && rest <= WAVE && full >= 1) {   // a short tail: one float per lane
         switch (full) {
-        case 1: hipLaunchKernelGGL((k_forward<T, 1, true, LOSS>), grid, blk, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((k_forward<T, 2, true, LOSS>), grid, blk, 0, st, a); break;
-        default: hipLaunchKernelGGL((k_forward<T, 3, true, LOSS>), grid, blk, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((k_forward<T, 1, true, LOSS>), grid, blk, 0, st, a, aux); break;
+        case 2: hipLaunchKernelGGL((k_forward<T, 2, true, LOSS>), grid, blk, 0, st, a, aux); break;
+        default: hipLaunchKernelGGL((k_forward<T, 3, true, LOSS>), grid, blk, 0, st, a, aux); break;
         }
         return;
     }
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     switch (iters) {
-    case 1: hipLaunchKernelGGL((k_forward<T, 1, false, LOSS>), grid, blk, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_forward<T, 2, false, LOSS>), grid, blk, 0, st, a); break;
-    case 3: hipLaunchKernelGGL((k_forward<T, 3, false, LOSS>), grid, blk, 0, st, a); break;
-    default: hipLaunchKernelGGL((k_forward<T, 4, false, LOSS>), grid, blk, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_forward<T, 1, false, LOSS>), grid, blk, 0, st, a, aux); break;
+    case 2: hipLaunchKernelGGL((k_forward<T, 2, false, LOSS>), grid, blk, 0, st, a, aux); break;
+    case 3: hipLaunchKernelGGL((k_forward<T, 3, false, LOSS>), grid, blk, 0, st, a, aux); break;
+    default: hipLaunchKernelGGL((k_forward<T, 4, false, LOSS>), grid, blk, 0, st, a, aux); break;
     }
 }
 
-void tn_launch_forward(const FwdArgs &a, hipStream_t st)
+void tn_launch_forward(const FwdArgs &a, const AuxWork *aux, hipStream_t st)
 {
+    AuxWork none;
+    if (!aux) {
+        tn_aux_none(none);
+        aux = &none;
+    }
     const bool loss = a.center_loss != nullptr;
-    if (a.dtype == 0) loss ? launch_forward_t<float, true>(a, st) : launch_forward_t<float, false>(a, st);
-    else loss ? launch_forward_t<bf16_t, true>(a, st) : launch_forward_t<bf16_t, false>(a, st);
+    if (a.dtype == 0) loss ? launch_forward_t<float, true>(a, *aux, st) : launch_forward_t<float, false>(a, *aux, st);
+    else loss ? launch_forward_t<bf16_t, true>(a, *aux, st) : launch_forward_t<bf16_t, false>(a, *aux, st);
 }
 
 // ---------------------------------------------------------------- segmented reduction
@@ -429,9 +442,14 @@ struct SegReducePair {
 };
 
 template <typename T, int NQ, bool TAIL, int TILE_OUT, int TILE_IN>
-__global__ void __launch_bounds__(BLOCK) k_segreduce(SegReducePair p)
+__global__ void __launch_bounds__(BLOCK) k_segreduce(SegReducePair p, AuxWork aux)
 {
-    const int b = blockIdx.x;
+    // the first aux.total workgroups carry the small jobs that ride with this launch
+    if ((int)blockIdx.x < aux.total) {
+        aux_block(aux, (int)blockIdx.x);
+        return;
+    }
+    const int b = (int)blockIdx.x - aux.total;
     if (b < p.blocks_in) segreduce_tile<float, NQ, TAIL, 1, TILE_IN>(p.in, b);
     else segreduce_tile<T, NQ, TAIL, 0, TILE_OUT>(p.out, b - p.blocks_in);
 }
@@ -569,7 +587,7 @@ __global__ void __launch_bounds__(FIXUP_THREADS) k_segfixup(SegReducePair p)
 // ITERS: float4 registers per lane of a whole row (the chaining kernels' layout); TAIL: the reduction
 // holds rows as ITERS-1 float4 and one float per lane instead (dimensions just above a multiple of 256)
 template <typename T, int ITERS, bool TAIL, int TILE_OUT, int TILE_IN>
-static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
+static void launch_segreduce_i(SegReducePair &p, const AuxWork &aux, hipStream_t st)
 {
     constexpr int NQ = TAIL ? ITERS - 1 : ITERS;
     const int tiles_out = p.out.n > 0 ? (p.out.n + TILE_OUT - 1) / TILE_OUT : 0;
@@ -578,8 +596,8 @@ static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
     if (tiles_in <= TN_SEG_CROSS_MIN) p.in.cross = nullptr;
     const int blocks_out = (tiles_out + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     p.blocks_in = (tiles_in + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    hipLaunchKernelGGL((k_segreduce<T, NQ, TAIL, TILE_OUT, TILE_IN>), dim3(p.blocks_in + blocks_out), dim3(BLOCK),
-                       0, st, p);
+    hipLaunchKernelGGL((k_segreduce<T, NQ, TAIL, TILE_OUT, TILE_IN>), dim3(aux.total + p.blocks_in + blocks_out),
+                       dim3(BLOCK), 0, st, p, aux);
     // Partials per block of tiles, for problems large enough that one row's chain could hold up the step:
     // up to TN_SEG_CROSS_MIN tiles even a row that takes every entry is walked by one workgroup in well
     // under a fifth of a millisecond, and the extra launch would cost every step several microseconds.
@@ -601,45 +619,50 @@ static void launch_segreduce_i(SegReducePair &p, hipStream_t st)
 }
 
 template <typename T, int ITERS, bool TAIL>
-static void launch_segreduce_t(SegReducePair &p, hipStream_t st)
+static void launch_segreduce_t(SegReducePair &p, const AuxWork &aux, hipStream_t st)
 {
     const bool so = tn_seg_tile(p.out.n) == 8, si = tn_seg_tile(p.in.n) == 8;
-    if (so) si ? launch_segreduce_i<T, ITERS, TAIL, 8, 8>(p, st) : launch_segreduce_i<T, ITERS, TAIL, 8, 32>(p, st);
-    else si ? launch_segreduce_i<T, ITERS, TAIL, 32, 8>(p, st) : launch_segreduce_i<T, ITERS, TAIL, 32, 32>(p, st);
+    if (so) si ? launch_segreduce_i<T, ITERS, TAIL, 8, 8>(p, aux, st) : launch_segreduce_i<T, ITERS, TAIL, 8, 32>(p, aux, st);
+    else si ? launch_segreduce_i<T, ITERS, TAIL, 32, 8>(p, aux, st) : launch_segreduce_i<T, ITERS, TAIL, 32, 32>(p, aux, st);
 }
 
 template <typename T>
-static void launch_segreduce_d(SegReducePair &p, int D, hipStream_t st)
+static void launch_segreduce_d(SegReducePair &p, int D, const AuxWork &aux, hipStream_t st)
 {
     const int iters = (D / 4 + WAVE - 1) / WAVE;
     const int rest = D - (iters - 1) * 4 * WAVE;   // elements in the last float4 register of a lane's row
     if (iters >= 2 && rest <= WAVE) {              // a short tail: one float per lane
         switch (iters) {
-        case 2: launch_segreduce_t<T, 2, true>(p, st); break;
-        case 3: launch_segreduce_t<T, 3, true>(p, st); break;
-        default: launch_segreduce_t<T, 4, true>(p, st); break;
+        case 2: launch_segreduce_t<T, 2, true>(p, aux, st); break;
+        case 3: launch_segreduce_t<T, 3, true>(p, aux, st); break;
+        default: launch_segreduce_t<T, 4, true>(p, aux, st); break;
         }
         return;
     }
     switch (iters) {
-    case 1: launch_segreduce_t<T, 1, false>(p, st); break;
-    case 2: launch_segreduce_t<T, 2, false>(p, st); break;
-    case 3: launch_segreduce_t<T, 3, false>(p, st); break;
-    default: launch_segreduce_t<T, 4, false>(p, st); break;
+    case 1: launch_segreduce_t<T, 1, false>(p, aux, st); break;
+    case 2: launch_segreduce_t<T, 2, false>(p, aux, st); break;
+    case 3: launch_segreduce_t<T, 3, false>(p, aux, st); break;
+    default: launch_segreduce_t<T, 4, false>(p, aux, st); break;
     }
 }
 
 // Either problem may be absent (NULL): the other one then runs alone.
-void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, hipStream_t st)
+void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, const AuxWork *aux, hipStream_t st)
 {
+    AuxWork none;
+    if (!aux) {
+        tn_aux_none(none);
+        aux = &none;
+    }
     SegReducePair p;
     memset(&p, 0, sizeof(p));
     if (out && out->n > 0) p.out = *out;
     if (in && in->n > 0) p.in = *in;
-    if (p.out.n <= 0 && p.in.n <= 0) return;
+    if (p.out.n <= 0 && p.in.n <= 0) return;   // callers attach jobs only to a mini-batch with pairs
     const int D = p.out.n > 0 ? p.out.D : p.in.D;
-    if (p.out.n > 0 && p.out.dtype != 0) launch_segreduce_d<bf16_t>(p, D, st);
-    else launch_segreduce_d<float>(p, D, st);
+    if (p.out.n > 0 && p.out.dtype != 0) launch_segreduce_d<bf16_t>(p, D, *aux, st);
+    else launch_segreduce_d<float>(p, D, *aux, st);
 }
 
 // ---------------------------------------------------------------- loss and the empty batch

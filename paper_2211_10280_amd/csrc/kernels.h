@@ -89,7 +89,8 @@ struct FwdArgs {
     float *center_loss;    // [n_centers] out (sum of the loss terms, not yet divided by P)
     float inv_P;
 };
-void tn_launch_forward(const FwdArgs &a, hipStream_t st);
+struct AuxWork;
+void tn_launch_forward(const FwdArgs &a, const AuxWork *aux, hipStream_t st);   // aux may be NULL
 
 // ---- stage 5: segmented reduction of rows (duplicates summed in sorted order)
 struct SegReduceArgs {
@@ -117,7 +118,7 @@ struct SegReduceArgs {
     const float *center_part;
 };
 // the W_out-side and the W_in-side problem of a mini-batch in one launch (either may be NULL)
-void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, hipStream_t st);
+void tn_launch_segreduce(const SegReduceArgs *out, const SegReduceArgs *in, const AuxWork *aux, hipStream_t st);
 
 void tn_launch_loss(const float *center_loss, int n_centers, float inv_P, float *mean_loss,
                     hipStream_t st);
@@ -150,6 +151,26 @@ struct ApplyArgs {
     int sr;
     u32 sr_k0, sr_k1, sr_serial;
 };
+// Small jobs that ride at the front of the grid of the forward pass or of the segmented reduction
+// (workgroups [0, total) of that launch): clearing the masks of the table update's index, copying a
+// prepared mini-batch's row index to the caller's buffers, indexing the sources [k_begin, k_end) of the
+// coming table update.  Clearing and indexing must not share a launch (the index needs cleared masks).
+struct AuxWork {
+    int total;               // clear_blocks + 2 * copy_blocks + 2 * (k_end - k_begin) * index_blocks
+    int clear_blocks;
+    u64 *clear_mask[2];      // masks to zero (both tables), clear_n entries each -- not necessarily apply's
+    size_t clear_n;
+    int copy_blocks;         // per table
+    RowIndexCopy copy;
+    int index_blocks;        // per (source, table)
+    int k_begin, k_end;
+    ApplyArgs apply;
+};
+void tn_aux_none(AuxWork &x);
+void tn_aux_add_clear(AuxWork &x, u64 *mask_in, u64 *mask_out, size_t n);
+void tn_aux_add_copy(AuxWork &x, const RowIndexCopy &c, i64 max_rows);
+void tn_aux_add_index(AuxWork &x, const ApplyArgs &a, int k_begin, int k_end);
+
 void tn_launch_apply_clear(const ApplyArgs &a, hipStream_t st);
 void tn_launch_apply_index(const ApplyArgs &a, int k_begin, int k_end, hipStream_t st);
 void tn_launch_apply_update(const ApplyArgs &a, hipStream_t st);

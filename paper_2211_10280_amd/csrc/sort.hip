@@ -7,6 +7,7 @@
 // into one contiguous segment, so the later reduction and the table update are free of
 // write conflicts and need no floating-point atomics; stability fixes the order of
 // the additions inside a segment.  All of this is integer work and bit-exact.
+#include "aux_dev.h"
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -351,13 +352,7 @@ void tn_launch_segments(SegProb p0, SegProb p1, i64 begin, i64 T, int w, int *st
 // workspace; this copies them into the buffers of the call that consumes them.
 __global__ void __launch_bounds__(BLOCK) k_copy_row_index(RowIndexCopy c)
 {
-    const RowIndexCopy::Side &s = c.side[blockIdx.y];
-    const int U = *s.src_n;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *s.dst_n = U;
-    for (int i = blockIdx.x * BLOCK + threadIdx.x; i <= U; i += gridDim.x * BLOCK) {
-        if (i < U) s.dst_ids[i] = s.src_ids[i];
-        if (s.dst_off) s.dst_off[i] = s.src_off[i];
-    }
+    aux_copy_row_index(c.side[blockIdx.y], (int)blockIdx.x, (int)gridDim.x);
 }
 
 void tn_launch_copy_row_index(const RowIndexCopy &c, i64 max_rows, hipStream_t st)
