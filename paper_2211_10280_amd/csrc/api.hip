@@ -74,8 +74,7 @@ Sizes sizes_of(const tensair_config &c)
     int kb = 1;
     while (((i64)1 << kb) < c.vocab) ++kb;
     s.key_bits = kb;
-    s.passes = (kb + 10) / 11;
-    s.bits = (kb + s.passes - 1) / s.passes;
+    tn_radix_shape(kb, &s.passes, &s.bits);
     s.nd = 1 << s.bits;
     s.nblk_out = (int)((s.Omax + TN_RADIX_TILE - 1) / TN_RADIX_TILE);
     s.nblk_in = (int)((s.Bmax + TN_RADIX_TILE - 1) / TN_RADIX_TILE);
@@ -515,8 +514,19 @@ static SegProb seg_prob(const tensair_model *m, const BatchSet &S, int side, int
 }
 
 // stable sort of both key lists by row id, then unique row ids and the segment of every sorted entry
+// LDS that the sort asks for beyond its counters where it runs next to the forward pass or the reductions of a
+// step (a preparation that was not tucked under a table update): 40 KB per workgroup, four workgroups per compute
+// unit, is the occupancy at which it was measured not to crowd them (hot-row configuration: 0.66 against 0.69 ms
+// per step with the sort at full occupancy); under a table update, or alone, it takes what it needs.
+#ifndef TN_SORT_LDS_BESIDE
+#define TN_SORT_LDS_BESIDE 40960
+#endif
+#ifndef TN_SORT_LDS_INLINE
+#define TN_SORT_LDS_INLINE 0
+#endif
+
 static void enqueue_sort_segments(tensair_model *m, BatchSet &S, const BatchWork &w, const RowIndexDst &in,
-                                  const RowIndexDst &out, hipStream_t st, hipStream_t st_mark)
+                                  const RowIndexDst &out, size_t min_lds, hipStream_t st, hipStream_t st_mark)
 {
     const tensair_config &c = m->cfg;
     const Sizes &s = m->sz;
@@ -537,7 +547,7 @@ static void enqueue_sort_segments(tensair_model *m, BatchSet &S, const BatchWork
     ri.nblk = (w.b.n_centers + TN_RADIX_TILE - 1) / TN_RADIX_TILE;
     ri.counts = S.counts_in;
     ri.totals = S.totals_in;
-    S.cur = tn_launch_radix_sort(ro, ri, s.key_bits, st, &S.kb);
+    S.cur = tn_launch_radix_sort(ro, ri, s.key_bits, min_lds, st, &S.kb);
     if (st_mark) mark(m, PF_SORT, st_mark);
 
     SegProb so = seg_prob(m, S, 0, (int)w.O), si = seg_prob(m, S, 1, w.b.n_centers);
@@ -583,7 +593,7 @@ static int enqueue_prepare(tensair_model *m, const Prefetched &d, bool late)
     m->pend_late = late;
     const RowIndexDst in = {S.ids_in, S.n_rows, S.off_in, tensair_capacity_in(&c, c.max_centers)};
     const RowIndexDst out = {S.ids_out, S.n_rows + 1, S.off_out, tensair_capacity_out(&c, c.max_centers)};
-    enqueue_sort_segments(m, S, w, in, out, m->side, nullptr);
+    enqueue_sort_segments(m, S, w, in, out, late ? TN_SORT_LDS_BESIDE : 0, m->side, nullptr);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(m->ev_prep, m->side));
     m->prep_ticket = ++m->side_ticket;
@@ -812,7 +822,7 @@ static int sgns_grad_impl(tensair_model *m, const int32_t *tokens, int64_t n_tok
         const RowIndexDst in = {grad_out->in.row_ids, grad_out->in.n_rows, seg_offsets_in, grad_out->in.capacity};
         const RowIndexDst out = {grad_out->out.row_ids, grad_out->out.n_rows, seg_offsets_out,
                                  grad_out->out.capacity};
-        enqueue_sort_segments(m, S, w, in, out, st, st);
+        enqueue_sort_segments(m, S, w, in, out, TN_SORT_LDS_INLINE, st, st);
         if (overlap) {
             HIP_TRY(hipStreamWaitEvent(st, m->ev_fwd, 0));
             m->main_ticket = m->side_ticket;

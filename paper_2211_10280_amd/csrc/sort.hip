@@ -11,7 +11,7 @@
 #include "dev_common.h"
 #include "kernels.h"
 
-#define RADIX_MAX_BITS 11
+#define RADIX_MAX_BITS TN_RADIX_MAX_BITS
 #define RADIX_MAX_ND (1 << RADIX_MAX_BITS)
 #define RADIX_IPT (TN_RADIX_TILE / BLOCK)   // keys per thread
 
@@ -28,9 +28,13 @@ struct RadixPass {
 };
 
 // per-block digit histogram: counts[d][b]
+// Dynamic LDS of the radix kernels: as many counters as the pass has digits.  The launcher may ask for more than
+// that to hold the kernels' occupancy down next to a kernel that should not be disturbed.
+extern __shared__ u32 radix_lds[];
+
 __global__ void __launch_bounds__(BLOCK) k_radix_hist(RadixPass a)
 {
-    __shared__ u32 h[RADIX_MAX_ND];
+    u32 *h = radix_lds;                                  // [nd]
     int b = blockIdx.x, pr = 0;
     if (b >= a.nblk[0]) { b -= a.nblk[0]; pr = 1; }
     const int nd = 1 << a.bits;
@@ -75,19 +79,19 @@ __global__ void __launch_bounds__(BLOCK) k_radix_rowscan(RadixPass a)
 // rank every key inside its block (stable), add the global base of its digit, scatter
 __global__ void __launch_bounds__(BLOCK) k_radix_scatter(RadixPass a)
 {
-    __shared__ u32 wh[WAVES_PER_BLOCK][RADIX_MAX_ND];  // per-wave digit counters -> bases
-    __shared__ u32 dbase[RADIX_MAX_ND];                // global exclusive base of every digit
     __shared__ u32 wsum[WAVES_PER_BLOCK];
     int b = blockIdx.x, pr = 0;
     if (b >= a.nblk[0]) { b -= a.nblk[0]; pr = 1; }
     const int nd = 1 << a.bits;
+    u32 *dbase = radix_lds;                              // [nd] global exclusive base of every digit
+    u32 *whp = radix_lds + nd;                           // [WAVES_PER_BLOCK][nd] per-wave digit counters -> bases
     const u32 dmask = (u32)nd - 1u;
     const int wave = threadIdx.x >> 6, lane = lane_id();
     const int n = a.n[pr], nblk = a.nblk[pr];
 
     for (int d = threadIdx.x; d < nd; d += BLOCK) {
 #pragma unroll
-        for (int w = 0; w < WAVES_PER_BLOCK; ++w) wh[w][d] = 0;
+        for (int w = 0; w < WAVES_PER_BLOCK; ++w) whp[w * nd + d] = 0;
     }
     // exclusive scan of the digit totals (nd <= 2048 = 256 threads x 8)
     {
@@ -135,8 +139,8 @@ __global__ void __launch_bounds__(BLOCK) k_radix_scatter(RadixPass a)
         u32 rank = (u32)__popcll(m & lt);
         u32 cnt = (u32)__popcll(m);
         u32 old = 0;
-        if (valid) old = wh[wave][d];
-        if (valid && rank == 0) wh[wave][d] = old + cnt;
+        if (valid) old = whp[wave * nd + d];
+        if (valid && rank == 0) whp[wave * nd + d] = old + cnt;
         loc[it] = old + rank;
     }
     __syncthreads();
@@ -148,8 +152,8 @@ __global__ void __launch_bounds__(BLOCK) k_radix_scatter(RadixPass a)
             u32 run = dbase[d] + counts[(size_t)d * nblk + b];
 #pragma unroll
             for (int w = 0; w < WAVES_PER_BLOCK; ++w) {
-                u32 c = wh[w][d];
-                wh[w][d] = run;
+                u32 c = whp[w * nd + d];
+                whp[w * nd + d] = run;
                 run += c;
             }
         }
@@ -163,18 +167,17 @@ __global__ void __launch_bounds__(BLOCK) k_radix_scatter(RadixPass a)
         int idx = wbase + it * WAVE + lane;
         if (idx < n) {
             u32 d = (key[it] >> a.shift) & dmask;
-            u32 pos = wh[wave][d] + loc[it];
+            u32 pos = whp[wave * nd + d] + loc[it];
             kout[pos] = key[it];
             vout[pos] = a.first ? (u32)idx : vin[idx];
         }
     }
 }
 
-int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t st, int *key_buf)
+int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, size_t min_lds_bytes, hipStream_t st, int *key_buf)
 {
-    if (key_bits < 1) key_bits = 1;
-    int passes = (key_bits + RADIX_MAX_BITS - 1) / RADIX_MAX_BITS;
-    int bits = (key_bits + passes - 1) / passes;
+    int passes, bits;
+    tn_radix_shape(key_bits, &passes, &bits);
     RadixProb p[2] = {p0, p1};
     int cur = 0;    // vals buffer holding the current order
     int kin = 0;    // keys buffer holding the current order
@@ -196,10 +199,13 @@ int tn_launch_radix_sort(RadixProb p0, RadixProb p1, int key_bits, hipStream_t s
         a.first = (pass == 0);
         int nblk = a.nblk[0] + a.nblk[1];
         int nd = 1 << bits;
-        hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(BLOCK), 0, st, a);
+        size_t lds_hist = (size_t)nd * 4, lds_scatter = (size_t)nd * 4 * (1 + WAVES_PER_BLOCK);
+        if (lds_hist < min_lds_bytes) lds_hist = min_lds_bytes;
+        if (lds_scatter < min_lds_bytes) lds_scatter = min_lds_bytes;
+        hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(BLOCK), lds_hist, st, a);
         hipLaunchKernelGGL(k_radix_rowscan, dim3((nd + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK, 2),
                            dim3(BLOCK), 0, st, a);
-        hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(BLOCK), 0, st, a);
+        hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(BLOCK), lds_scatter, st, a);
         cur ^= 1;
         kin = kout;
     }
