@@ -151,20 +151,9 @@ def main():
     assert len(apply_ms) == S, (len(apply_ms), S)
     n_launch = len(apply_ms)
 
-    # ---- streaming ceiling of this machine: a plain 1 GiB copy (reads 1 GiB, writes 1 GiB)
-    nbytes = 1 << 30
-    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        B.tensair_copy_probe(dst, src, nbytes)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(10):
-        B.tensair_copy_probe(dst, src, nbytes)
-    ev1.record()
-    torch.cuda.synchronize()
-    copy_GBps = 2 * nbytes * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del src, dst
+    # ---- streaming ceilings of this machine: 1 GiB per stream; plain copy (also the calibration of the HBM byte
+    #      counters), copy around the caches, read only, and three reads per write (the read share of k_apply)
+    copy_GBps, ceilings = streaming_ceilings(B, torch)
 
     n_pairs = sum(pairs[Wm:])
     value = n_pairs / elapsed
@@ -221,6 +210,7 @@ def main():
                    "stochastic_rounding": cfg.stochastic_rounding, "resampled_negatives": cfg.resample},
         "step_hbm_frac": step_bytes / elapsed / HBM_PEAK,
         "measured_copy_GBps": copy_GBps,
+        "measured_streaming_GBps": ceilings,
         "step_algorithmic_bytes": step_bytes / S,
         "roofline": {"bound": "hbm", "kernel": "k_apply", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": traffic,
@@ -252,6 +242,28 @@ def main():
                                          f"untimed, as on the GPU",
                                "host_cpus": os.cpu_count()}
     print(json.dumps(out), flush=True)
+
+
+def streaming_ceilings(B, torch, reps=10):
+    """(plain copy GB/s, {mix: GB/s}) of the library's streaming probes over 1 GiB per stream."""
+    nbytes = 1 << 30
+    src = torch.empty(3 * nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    moved = {0: 2 * nbytes, 1: 2 * nbytes, 2: nbytes, 3: 4 * nbytes}
+    names = {0: "copy", 1: "copy_nontemporal", 2: "read_only", 3: "read3_write1"}
+    out = {}
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for mode in (0, 1, 2, 3):
+        for _ in range(3):
+            B.tensair_stream_probe(dst, src, nbytes, mode)
+        ev0.record()
+        for _ in range(reps):
+            B.tensair_stream_probe(dst, src, nbytes, mode)
+        ev1.record()
+        torch.cuda.synchronize()
+        out[names[mode]] = round(moved[mode] * reps / (ev0.elapsed_time(ev1) * 1e-3) / 1e9, 1)
+    del src, dst
+    return out["copy"], out
 
 
 def bench_grad_add(args, cfg, tok, counts):

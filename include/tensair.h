@@ -59,9 +59,13 @@ enum {
 
 #define TENSAIR_MAX_DIM 1024  /* dim must be a multiple of 4, 4..1024 */
 #define TENSAIR_MAX_PEERS 31
+/* Largest sizes that one launch of the update kernels covers (2^32 threads): a model of at most
+ * TENSAIR_MAX_VOCAB rows, a dense parameter vector of at most TENSAIR_MAX_DENSE elements. */
+#define TENSAIR_MAX_VOCAB 268435392LL      /* 2^28 - 64 */
+#define TENSAIR_MAX_DENSE 8589934592LL     /* 2^33 */
 
 typedef struct {
-    int64_t vocab;       /* V, 1 .. 2^31-1 */
+    int64_t vocab;       /* V, 1 .. TENSAIR_MAX_VOCAB */
     int32_t dim;         /* D, multiple of 4 */
     int32_t row_stride;  /* elements between consecutive table rows, >= dim, multiple of 4 */
     int32_t dtype;       /* TENSAIR_F32 | TENSAIR_BF16 */
@@ -206,7 +210,7 @@ int tensair_grad_add(tensair_model *m, const tensair_sparse_grad *a, const tensa
  * every variable receives gradient), for the own gradient and the gradients received from peers
  * at once: theta[i] <- theta[i] - lr * (grads[0][i] + ... + grads[n_grads-1][i]), the sum taken
  * in fp32 in that order, one rounding on store (round-to-nearest-even for bf16).
- * theta: DEVICE [n] of dtype, 16-byte aligned.  grads: HOST array of n_grads DEVICE pointers to
+ * theta: DEVICE [n] of dtype, 16-byte aligned, n <= TENSAIR_MAX_DENSE.  grads: HOST array of n_grads DEVICE pointers to
  * fp32 [n] blocks, each 16-byte aligned, n_grads <= TENSAIR_MAX_PEERS + 1.  Needs no model handle. */
 int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *const *grads, int32_t n_grads,
                         float lr, void *stream);
@@ -300,6 +304,14 @@ int tensair_profile_read(tensair_model *m, int32_t *tags, float *ms, int32_t max
  * aligned, bytes a multiple of 16, no overlap).  Reads `bytes` and writes `bytes`: the
  * streaming-bandwidth ceiling of the box and the calibration of its HBM byte counters. */
 int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Measurement aid: streaming kernels with other mixes of reads and writes over `bytes` (DEVICE, 16-byte
+ * aligned, a multiple of 16, no overlap), the ceilings that kernels of the same mix are set against.
+ * mode 0: the plain copy of tensair_copy_probe; 1: the same copy around the caches (non-temporal loads and
+ * stores); 2: read only -- src is read, dst receives one 16-byte chunk per workgroup (at most 256 KiB);
+ * 3: three reads per write -- dst[i] = src[i] + src[n + i] + src[2n + i] over fp32 elements, src holding
+ * 3 * bytes, around the caches (the read share of a table update that merges several gradient blocks). */
+int tensair_stream_probe(void *dst, const void *src, size_t bytes, int32_t mode, void *stream);
 
 /* tensair_dasgd_apply for callers that cannot allocate device memory and hold no model handle: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same update, same

@@ -37,6 +37,22 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+_SAN_SRC = os.path.join(_HERE, "sanitize_check.c")
+_SAN_BIN = os.path.join(_HERE, "sanitize_check")
+
+
+def build_sanitize_check(force: bool = False) -> str:
+    """Compile ``sanitize_check.c`` (the oracle's C source driven over small inputs) with gcc's address and
+    undefined-behaviour sanitizers into a program of its own; the CPU tests run it."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SAN_SRC))
+    if force or not os.path.exists(_SAN_BIN) or os.path.getmtime(_SAN_BIN) < newest:
+        subprocess.check_call(
+            ["gcc", "-O1", "-g", "-ffp-contract=off", "-fno-fast-math", "-fsanitize=address,undefined",
+             "-static-libasan", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+             "-o", _SAN_BIN, _SAN_SRC, "-lm"])
+    return _SAN_BIN
+
+
 _lib = None
 
 

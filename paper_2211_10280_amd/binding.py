@@ -19,6 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libtensair.so")
 F32, BF16 = 0, 1
 OK, EINVAL, ECAPACITY, EHIP, EDATA = 0, -1, -2, -3, -4
 MAX_PEERS = 31
+MAX_VOCAB = (1 << 28) - 64
+MAX_DENSE = 1 << 33
 STATIC_MAX_VOCAB = 1 << 21
 STATIC_MAX_PEERS = 15
 RESAMPLE_NEGATIVES = 1
@@ -31,7 +33,7 @@ SYMBOLS = [
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
     "tensair_prefetch", "tensair_grad_add", "tensair_dense_apply", "tensair_lookup",
     "tensair_cosine_difference", "tensair_grad_pack", "tensair_dasgd_apply_packed", "tensair_step_packed",
-    "tensair_dasgd_apply_static",
+    "tensair_dasgd_apply_static", "tensair_stream_probe",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -127,6 +129,8 @@ def lib():
         L.tensair_profile_read.restype = C.c_int
         L.tensair_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
         L.tensair_copy_probe.restype = C.c_int
+        L.tensair_stream_probe.argtypes = [vp, vp, C.c_size_t, i32, vp]
+        L.tensair_stream_probe.restype = C.c_int
         L.tensair_last_error.argtypes = []
         L.tensair_last_error.restype = C.c_char_p
         _lib = L
@@ -360,6 +364,10 @@ def tensair_profile_read(h, max_records: int = 65536):
 
 def tensair_copy_probe(dst, src, nbytes: int, stream=None):
     _check(lib().tensair_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def tensair_stream_probe(dst, src, nbytes: int, mode: int, stream=None):
+    _check(lib().tensair_stream_probe(_ptr(dst), _ptr(src), nbytes, mode, _stream(stream)))
 
 
 def tensair_model_destroy(h):

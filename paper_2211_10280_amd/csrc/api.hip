@@ -50,7 +50,7 @@ bool config_ok(const tensair_config *c, const char **why)
 {
     *why = nullptr;
     if (!c) { *why = "cfg is NULL"; return false; }
-    if (c->vocab < 1 || c->vocab > 0x7FFFFFFFLL) { *why = "vocab out of range"; return false; }
+    if (c->vocab < 1 || c->vocab > TENSAIR_MAX_VOCAB) { *why = "vocab outside 1..TENSAIR_MAX_VOCAB"; return false; }
     if (c->dim < 4 || c->dim > TENSAIR_MAX_DIM || c->dim % 4) { *why = "dim must be a multiple of 4 in 4..1024"; return false; }
     if (c->row_stride < c->dim || c->row_stride % 4) { *why = "row_stride must be >= dim and a multiple of 4"; return false; }
     if (c->dtype != TENSAIR_F32 && c->dtype != TENSAIR_BF16) { *why = "unknown dtype"; return false; }
@@ -1148,7 +1148,7 @@ int tensair_dense_apply(void *theta, int32_t dtype, int64_t n, const float *cons
 {
     if (!theta || (n_grads > 0 && !grads)) return fail(TENSAIR_EINVAL, "NULL pointer argument");
     if (dtype != TENSAIR_F32 && dtype != TENSAIR_BF16) return fail(TENSAIR_EINVAL, "unknown dtype");
-    if (n < 0 || n > ((int64_t)1 << 40)) return fail(TENSAIR_EINVAL, "n outside 0..2^40");
+    if (n < 0 || n > TENSAIR_MAX_DENSE) return fail(TENSAIR_EINVAL, "n outside 0..TENSAIR_MAX_DENSE");
     if (n_grads < 0 || n_grads > TENSAIR_MAX_PEERS + 1)
         return fail(TENSAIR_ECAPACITY, "n_grads %d outside 0..%d", n_grads, TENSAIR_MAX_PEERS + 1);
     if (!(lr == lr)) return fail(TENSAIR_EINVAL, "lr is NaN");
@@ -1238,6 +1238,16 @@ int tensair_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
     if (!dst || !src || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15))
         return fail(TENSAIR_EINVAL, "copy_probe: pointers and size must be multiples of 16");
     tn_launch_copy_probe(dst, src, bytes, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return TENSAIR_OK;
+}
+
+int tensair_stream_probe(void *dst, const void *src, size_t bytes, int32_t mode, void *stream)
+{
+    if (!dst || !src || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15))
+        return fail(TENSAIR_EINVAL, "stream_probe: pointers and size must be multiples of 16");
+    if (mode < 0 || mode > 3) return fail(TENSAIR_EINVAL, "stream_probe: mode must be 0..3");
+    tn_launch_stream_probe(dst, src, bytes, mode, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return TENSAIR_OK;
 }

@@ -110,7 +110,7 @@ static void launch_lookup_t(const LookupArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     i64 want = (a.n + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    const int blocks = (int)(want > 0x3FFFFFFF ? 0x3FFFFFFF : want);
+    const int blocks = (int)(want > TN_MAX_BLOCKS ? TN_MAX_BLOCKS : want);
     switch (iters) {
     case 1: hipLaunchKernelGGL((k_lookup<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
     case 2: hipLaunchKernelGGL((k_lookup<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
@@ -160,7 +160,7 @@ static void launch_cosine_t(const CosineArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     i64 want = (a.V + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    const int blocks = (int)(want > 0x3FFFFFFF ? 0x3FFFFFFF : want);
+    const int blocks = (int)(want > TN_MAX_BLOCKS ? TN_MAX_BLOCKS : want);
     switch (iters) {
     case 1: hipLaunchKernelGGL((k_cosine_diff<T, 1>), dim3(blocks), dim3(BLOCK), 0, st, a); break;
     case 2: hipLaunchKernelGGL((k_cosine_diff<T, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); break;

@@ -9,6 +9,7 @@ typedef uint64_t u64;
 typedef int64_t i64;
 
 #define TN_MAX_SRC 32     // own + up to 31 peers
+#define TN_MAX_BLOCKS ((1 << 24) - 1)   // workgroups of 256 threads that one launch may have (2^32 threads in all)
 // sorted entries per wave in the segmented reduction: small problems get small tiles so that
 // enough waves exist to hide the latency of the row loads
 static inline int tn_seg_tile(i64 n) { return n <= 65536 ? 8 : 32; }
@@ -250,6 +251,8 @@ void tn_launch_cosine_diff(const CosineArgs &a, hipStream_t st);
 
 // ---- measurement aid: plain copy of `bytes` (multiple of 16)
 void tn_launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);
+// mode 0 plain copy, 1 copy around the caches, 2 read only, 3 three reads per write (src holds 3 * bytes)
+void tn_launch_stream_probe(void *dst, const void *src, size_t bytes, int mode, hipStream_t st);
 
 // ---- host-side helpers shared by the files that hold C-ABI entry points
 // records the thread-local message of tensair_last_error and returns `code`

@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
         pytest.fail("libtensair.so has not been built (python -m paper_2211_10280_amd.build)")
     L = C.CDLL(B.LIB_PATH)
     names = _declared()
-    assert len(names) >= 25
+    assert len(names) >= 26
     for n in names:
         assert hasattr(L, n), n
     assert sorted(B.SYMBOLS) == names        # the binding forwards to exactly these
@@ -36,6 +36,10 @@ def test_host_side_argument_checks():
     assert B.tensair_capacity_out(good, 64) == 1000          # min(V, 2*2*64*6 = 1536)
     assert B.tensair_capacity_out(good, 10) == 240
     assert B.tensair_workspace_bytes(B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7, B.RESAMPLE_NEGATIVES)) > 0
+    # sizes beyond what one launch of the update kernels covers are refused, the largest allowed ones are not
+    assert B.tensair_workspace_bytes(B.Config(B.MAX_VOCAB, 4, 4, B.F32, 1, 0, 1, 0, 0, 7)) > 0
+    with pytest.raises(B.TensairError):
+        B.tensair_workspace_bytes(B.Config(B.MAX_VOCAB + 1, 4, 4, B.F32, 1, 0, 1, 0, 0, 7))
     for bad in (B.Config(0, 32, 32, B.F32, 2, 5, 64, 0, 0, 7),      # vocab
                 B.Config(1000, 30, 32, B.F32, 2, 5, 64, 0, 0, 7),    # dim not a multiple of 4
                 B.Config(1000, 32, 28, B.F32, 2, 5, 64, 0, 0, 7),    # stride < dim
@@ -68,6 +72,7 @@ def test_host_side_argument_checks_of_the_further_entry_points():
     assert L.tensair_dense_apply(None, B.F32, 16, ptrs, 1, 0.1, None) == B.EINVAL
     assert L.tensair_dense_apply(aligned, 7, 16, ptrs, 1, 0.1, None) == B.EINVAL
     assert L.tensair_dense_apply(aligned, B.F32, -1, ptrs, 1, 0.1, None) == B.EINVAL
+    assert L.tensair_dense_apply(aligned, B.F32, B.MAX_DENSE + 4, ptrs, 1, 0.1, None) == B.EINVAL
     assert L.tensair_dense_apply(aligned, B.F32, 16, ptrs, B.MAX_PEERS + 2, 0.1, None) == B.ECAPACITY
     assert L.tensair_dense_apply(aligned, B.F32, 16, ptrs, 1, float("nan"), None) == B.EINVAL
     assert L.tensair_dense_apply(aligned + 4, B.F32, 16, ptrs, 1, 0.1, None) == B.EINVAL
@@ -88,6 +93,8 @@ def test_host_side_argument_checks_of_the_further_entry_points():
     assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 6, 8, B.F32, None, None, 0, 0.1, None, None) == B.EINVAL
     assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 4, 4, B.F32, None, None, 1, 0.1, None, None) == B.EINVAL
     assert L.tensair_dasgd_apply_static(aligned, aligned, 64, 4, 4, B.F32, None, None, 0, 0.1, None, None) == B.OK   # nothing to apply
+    assert L.tensair_stream_probe(aligned, aligned + 4, 64, 0, None) == B.EINVAL
+    assert L.tensair_stream_probe(aligned, aligned, 64, 7, None) == B.EINVAL
     # calls that need a model
     assert L.tensair_lookup(None, 0, None, 0, None, None) == B.EINVAL
     assert L.tensair_grad_add(None, None, None, None, None) == B.EINVAL

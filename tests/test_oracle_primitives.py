@@ -246,3 +246,15 @@ def test_staleness_worked_example_of_the_paper():
         assert oracle.staleness(gi.split(), gj.split()) == int(want), name
     # symmetric difference, not a one-sided difference
     assert oracle.staleness({"a", "b"}, {"b", "c", "d"}) == 3
+
+
+# ------------------------------------------------------------------ sanitizers
+def test_oracle_runs_clean_under_address_and_ub_sanitizers():
+    """The oracle's C source, driven over small inputs that reach its edges, under gcc's address and
+    undefined-behaviour sanitizers (a program of its own: an out-of-bounds access, a leak or an overflow
+    ends it with a report and a non-zero status)."""
+    import subprocess
+    exe = oracle.build_sanitize_check()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "sanitize_check: ok" in r.stdout and "ERROR" not in r.stderr
