@@ -50,8 +50,8 @@ def main():
                     help="every step self-contained (default: the next mini-batch is handed to tensair_prefetch "
                          "after each step, as it would be waiting in the worker's input queue)")
     ap.add_argument("--row-stride", type=int, default=None,
-                    help="elements between table rows (default: dim; a multiple of 32 fp32 / 64 bf16 elements "
-                         "starts every row on a 128-byte line)")
+                    help="elements between table rows (default: the pitch that starts every row on a 128-byte "
+                         "line, tensair_aligned_row_stride: 320 for dim 300 in fp32; pass the dim for dense rows)")
     ap.add_argument("--stochastic-rounding", action="store_true",
                     help="bf16 tables rounded stochastically by the table update (a variant; workload 5)")
     ap.add_argument("--resample-negatives", action="store_true",

@@ -128,6 +128,12 @@ typedef struct {
     tensair_packed_rows in, out;
 } tensair_packed_grad;
 
+/* The row pitch (in elements) at which every table row starts on a 128-byte line: the smallest multiple
+ * of 128 bytes that holds dim elements of dtype (dim 300 in fp32: 320).  Any row_stride >= dim that is a
+ * multiple of 4 is accepted; with this one a row shares no cache line with its neighbours, which the table
+ * update measurably likes (the padding columns are never read or written).  Returns -1 for a bad argument. */
+int32_t tensair_aligned_row_stride(int32_t dim, int32_t dtype);
+
 /* Bytes of DEVICE workspace tensair_model_init needs for `cfg` (0 if cfg is invalid). */
 size_t tensair_workspace_bytes(const tensair_config *cfg);
 

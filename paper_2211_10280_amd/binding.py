@@ -33,7 +33,7 @@ SYMBOLS = [
     "tensair_last_error", "tensair_profile", "tensair_profile_read", "tensair_copy_probe",
     "tensair_prefetch", "tensair_grad_add", "tensair_dense_apply", "tensair_lookup",
     "tensair_cosine_difference", "tensair_grad_pack", "tensair_dasgd_apply_packed", "tensair_step_packed",
-    "tensair_dasgd_apply_static", "tensair_stream_probe",
+    "tensair_dasgd_apply_static", "tensair_stream_probe", "tensair_aligned_row_stride",
 ]
 
 PROFILE_TAGS = {1: "keys", 2: "forward", 3: "sort", 4: "segments", 5: "reduce_in", 6: "reduce_out",
@@ -75,6 +75,8 @@ def lib():
                 "(there is no fallback path)")
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, u32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32
+        L.tensair_aligned_row_stride.argtypes = [i32, i32]
+        L.tensair_aligned_row_stride.restype = i32
         L.tensair_workspace_bytes.argtypes = [C.POINTER(Config)]
         L.tensair_workspace_bytes.restype = C.c_size_t
         L.tensair_capacity_in.argtypes = [C.POINTER(Config), i32]
@@ -216,6 +218,13 @@ class PackedBuffers(GradBuffers):
 
 
 # ---------------------------------------------------------------- C entry points, same names
+def tensair_aligned_row_stride(dim: int, dtype: int) -> int:
+    n = lib().tensair_aligned_row_stride(dim, dtype)
+    if n < 0:
+        raise TensairError(EINVAL, "aligned_row_stride: bad dim or dtype")
+    return n
+
+
 def tensair_workspace_bytes(cfg: Config) -> int:
     n = lib().tensair_workspace_bytes(C.byref(cfg))
     if n == 0:

@@ -351,6 +351,13 @@ extern "C" {
 
 const char *tensair_last_error(void) { return g_err; }
 
+int32_t tensair_aligned_row_stride(int32_t dim, int32_t dtype)
+{
+    if (dim < 1 || dim > TENSAIR_MAX_DIM || (dtype != TENSAIR_F32 && dtype != TENSAIR_BF16)) return -1;
+    const int per_line = dtype == TENSAIR_F32 ? 32 : 64;   // elements in 128 bytes
+    return (dim + per_line - 1) / per_line * per_line;
+}
+
 size_t tensair_workspace_bytes(const tensair_config *cfg)
 {
     const char *why;

@@ -27,13 +27,19 @@ import workload as W
 class DasgdWorker:
     def __init__(self, cfg: W.Config, tokens: np.ndarray, counts: np.ndarray, device="cuda", prefetch=True,
                  row_stride=None, bf16_messages=False, tables=None):
-        """tables: (w_in, w_out) device tensors of a pre-trained model to train on in place; None: a fresh one."""
+        """tables: (w_in, w_out) device tensors of a pre-trained model to train on in place; None: a fresh one.
+        row_stride: elements between table rows; None: the pitch that starts every row on a 128-byte line
+        (of the given tables, if any)."""
         self.cfg = cfg
         self.bf16_messages = bf16_messages
         self.prefetch = prefetch     # announce coming mini-batches with tensair_prefetch
         self.announced = -1          # last step whose mini-batch has been announced
         self.device = device
         dt = B.F32 if cfg.dtype == "f32" else B.BF16
+        if tables is not None:
+            row_stride = tables[0].shape[1]
+        elif row_stride is None:
+            row_stride = B.tensair_aligned_row_stride(cfg.dim, dt)
         flags = (B.RESAMPLE_NEGATIVES if cfg.resample else 0) | (B.STOCHASTIC_ROUNDING if cfg.stochastic_rounding else 0)
         self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(device)
         self.model = B.Model(cfg.vocab, cfg.dim, dt, cfg.window, cfg.negatives, cfg.batch,
@@ -152,7 +158,9 @@ class DasgdWorker:
         self.announced = -1
 
     def tables_to_host(self):
-        w_in, w_out = self.model.w_in, self.model.w_out
+        """The two tables without their padding columns, as numpy arrays (bf16 as uint16 bits)."""
+        D = self.cfg.dim
+        w_in, w_out = self.model.w_in[:, :D].contiguous(), self.model.w_out[:, :D].contiguous()
         if self.cfg.dtype == "bf16":
             return (w_in.view(torch.int16).cpu().numpy().view(np.uint16),
                     w_out.view(torch.int16).cpu().numpy().view(np.uint16))

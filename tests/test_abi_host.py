@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
         pytest.fail("libtensair.so has not been built (python -m paper_2211_10280_amd.build)")
     L = C.CDLL(B.LIB_PATH)
     names = _declared()
-    assert len(names) >= 26
+    assert len(names) >= 27
     for n in names:
         assert hasattr(L, n), n
     assert sorted(B.SYMBOLS) == names        # the binding forwards to exactly these
@@ -32,6 +32,9 @@ def test_host_side_argument_checks():
     L = B.lib()
     good = B.Config(1000, 32, 32, B.F32, 2, 5, 64, 0, 0, 7)
     assert B.tensair_workspace_bytes(good) > 2 * 1000 * 4
+    assert B.tensair_aligned_row_stride(300, B.F32) == 320 and B.tensair_aligned_row_stride(300, B.BF16) == 320
+    assert B.tensair_aligned_row_stride(512, B.BF16) == 512 and B.tensair_aligned_row_stride(4, B.F32) == 32
+    assert L.tensair_aligned_row_stride(0, B.F32) == -1 and L.tensair_aligned_row_stride(8, 9) == -1
     assert B.tensair_capacity_in(good, 64) == 64
     assert B.tensair_capacity_out(good, 64) == 1000          # min(V, 2*2*64*6 = 1536)
     assert B.tensair_capacity_out(good, 10) == 240

@@ -407,13 +407,23 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
         have changed, per table -- a run in which nothing moves proves nothing."""
     tok, counts = _stream(cfg)
     tables = dev = None
+    D = cfg.dim
     if pretrained is not None:
-        tables = _random_tables(cfg.vocab, cfg.dim, cfg.dim, cfg.dtype, seed=100 + cfg.idx, scale=pretrained)
-        dev = (to_dev(tables[0]), to_dev(tables[1]))
+        # the oracle keeps dense rows; the GPU side gets the same values at the row pitch the trainer chooses
+        # (every row on a 128-byte line: 320 elements for dim 300), padding columns zero
+        tables = _random_tables(cfg.vocab, D, D, cfg.dtype, seed=100 + cfg.idx, scale=pretrained)
+        stride = B.tensair_aligned_row_stride(D, DT[cfg.dtype][0])
+        dev = []
+        for w in tables:
+            t = torch.zeros((cfg.vocab, stride), dtype=DT[cfg.dtype][2], device="cuda")
+            t[:, :D] = to_dev(w)
+            dev.append(t)
+        dev = tuple(dev)
     gw = DasgdWorker(cfg, tok, counts, prefetch=prefetch, bf16_messages=bf16_messages, tables=dev)
     ow = OracleWorker(cfg, tok, counts, threads=threads, bf16_messages=bf16_messages, tables=tables)
     w0 = (to_dev(ow.W_in), to_dev(ow.W_out))
-    assert torch.equal(gw.model.w_in, w0[0]) and torch.equal(gw.model.w_out, w0[1])     # same initial model, bit for bit
+    live = lambda: (gw.model.w_in[:, :D], gw.model.w_out[:, :D])        # the tables without their padding
+    assert torch.equal(live()[0], w0[0]) and torch.equal(live()[1], w0[1])     # same initial model, bit for bit
     bf16 = cfg.dtype == "bf16"
     worst_rows = 0.0
     peak = [ow.W_in & 0x7FFF, ow.W_out & 0x7FFF] if bf16 and not forced else None
@@ -422,8 +432,8 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
     for t in range(steps):
         if forced:
             before = (to_dev(ow.W_in), to_dev(ow.W_out))
-            gw.model.w_in.copy_(before[0])
-            gw.model.w_out.copy_(before[1])
+            live()[0].copy_(before[0])
+            live()[1].copy_(before[1])
         gw.step(want_loss=True)
         grads = ow.step()
         if peak is not None:
@@ -451,7 +461,7 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
             worst_rows = max(worst_rows, rows_rel(br, ow.sent.gin.rows), rows_rel(bq, ow.sent.gout.rows))
         if forced:
             # this step alone, from identical inputs, against the bars of a single application
-            for ti, (name, got_t, want) in enumerate(zip(names, (gw.model.w_in, gw.model.w_out), (ow.W_in, ow.W_out))):
+            for ti, (name, got_t, want) in enumerate(zip(names, live(), (ow.W_in, ow.W_out))):
                 want_t = to_dev(want)
                 st = ulp_stats_t(got_t, want_t, before[ti])
                 at_max, _ = ulp_err_at_t(got_t, want_t, before[ti])
@@ -488,7 +498,9 @@ def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_b
     # bf16: once the two sides' tables differ by a rounding (<= 2 ulp is allowed), the gradients
     # computed from them differ by up to one bf16 ulp (2^-8) of their inputs
     assert worst_rows <= (TOL_ROWS if cfg.dtype == "f32" or forced else 2.0 ** -8)
-    for ti, (got_t, want, name) in enumerate(((gw.model.w_in, ow.W_in, "W_in"), (gw.model.w_out, ow.W_out, "W_out"))):
+    for full in (gw.model.w_in, gw.model.w_out):                       # the padding columns stay zero
+        assert full.shape[1] == D or not full[:, D:].any().item()
+    for ti, (got_t, want, name) in enumerate(((live()[0], ow.W_in, "W_in"), (live()[1], ow.W_out, "W_out"))):
         want_t = to_dev(want)
         st = ulp_stats_t(got_t, want_t, w0[ti])
         n_touched = int(touched[ti].sum()) * cfg.dim
