@@ -151,8 +151,11 @@ __device__ __forceinline__ void update_row(T *wrow, u64 S, u64 rows_ptr, u32 pos
     else store_row<T, ITERS>(wrow, w, C4, lane);
 }
 
+// occupancy cap, so that the kernels of the second stream (the preparation of the next mini-batch) find wave
+// slots next to this one; measured with table rows on 128-byte lines: 5 / 6 / 7 / 8 waves per SIMD give a step of
+// 0.846 / 0.836 / 0.823 / 0.828 ms at a million words, and no difference at two million (3.46-3.49 ms)
 #ifndef APPLY_MAX_WAVES
-#define APPLY_MAX_WAVES 6
+#define APPLY_MAX_WAVES 7
 #endif
 template <typename T, int ITERS, int G, bool STREAM, bool PACKED>
 __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(1, APPLY_MAX_WAVES)))
