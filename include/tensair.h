@@ -274,9 +274,12 @@ int tensair_step_packed(tensair_model *m, const int32_t *tokens, int64_t n_token
  * segments, unique row ids -- is prepared ahead of time on the library's own stream, next to
  * whatever the caller's stream is doing (in TensAIR's dataflow, Section 3, mini-batches queue
  * up at the Model operator: the coming ones are known while the current one trains).
- * Up to two announcements are kept, in order: the first is prepared at once; a second one is
- * prepared at the start of the gradient call that consumes the first (next to that call's
- * forward pass), a third replaces the second.  A gradient call on this model uses the
+ * Up to two announcements are kept, in order.  When the first is prepared is the library's choice: at
+ * once if the mini-batch is small (up to 2^20 context and negative occurrences: its sort is bound by
+ * latency and fits beside whatever runs), else by the gradient call that consumes it.  A second one is
+ * prepared during the gradient call that consumes the first -- under that call's table update if
+ * tensair_step expects a long one, else beside its forward pass if small; a third replaces the second.
+ * A gradient call on this model uses the
  * prepared data if its (tokens, n_tokens, center_begin, n_centers, epoch) and the model's
  * worker id are those of the oldest announcement -- its results are then bit-identical to
  * those of a call without prefetch -- and otherwise drops every announcement.
