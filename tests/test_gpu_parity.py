@@ -1064,11 +1064,19 @@ def test_prefetch_gives_the_same_bits():
     m.close()
 
 
-@pytest.mark.parametrize("idx", [3, 5])
-def test_training_with_and_without_prefetch_is_bit_identical(idx):
+@pytest.mark.parametrize("name,idx,kw", [
+    ("cfg3_pf", 3, dict(vocab=20_000, tokens=300_000, batch=256)),
+    ("cfg5_pf", 5, dict(vocab=20_000, tokens=300_000, batch=256)),
+    # mini-batches above 2^20 occurrences are not prepared beside a step; with a long table update to follow
+    # (wide rows, 15 peers) the one after the current is still prepared under that update ...
+    ("cfg5_big_long_update", 5, dict(vocab=300_000, tokens=1_000_000, batch=12_000)),
+    # ... and with a short one (narrow rows, 1 peer) every announcement is left to the consuming call
+    ("cfg2_big_short_update", 2, dict(vocab=50_000, dim=32, tokens=1_000_000, batch=20_000, peers=1)),
+])
+def test_training_with_and_without_prefetch_is_bit_identical(name, idx, kw):
     """Several DASGD steps (peers, staleness) with the next mini-batch prefetched after every step against
     the same steps without: own gradients, losses and final tables agree bit for bit."""
-    cfg = W.CONFIGS[idx].scaled(name=f"cfg{idx}_pf", vocab=20_000, tokens=300_000, batch=256)
+    cfg = W.CONFIGS[idx].scaled(name=name, **kw)
     tok, counts = W.make_stream(cfg)
     a = DasgdWorker(cfg, tok, counts, prefetch=True)
     b = DasgdWorker(cfg, tok, counts, prefetch=False)
@@ -1082,6 +1090,33 @@ def test_training_with_and_without_prefetch_is_bit_identical(idx):
         assert np.array_equal(x, y)
     a.model.close()
     b.model.close()
+
+
+# ------------------------------------------------------------------ measurement aids
+def test_streaming_probes_move_what_they_say():
+    """The probes behind the bandwidth ceilings of the benchmark line: both copies reproduce their source, the
+    three-reads-per-write probe writes the sum of its three source blocks, the read-only probe writes nothing
+    beyond one chunk per workgroup."""
+    n = 1 << 20                                             # floats per block (4 MiB), not a multiple of the grid
+    n -= 12
+    src = torch.randn(3 * n, device="cuda")
+    for mode in (0, 1):
+        dst = torch.zeros(n + 8, device="cuda")
+        B.tensair_stream_probe(dst, src, 4 * n, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src[:n]) and not dst[n:].any().item()
+    dst = torch.zeros(n + 8, device="cuda")
+    B.tensair_stream_probe(dst, src, 4 * n, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], (src[:n] + src[n:2 * n]) + src[2 * n:]) and not dst[n:].any().item()
+    dst = torch.full((1 << 16,), 7.0, device="cuda")        # 256 KiB: the most the read-only probe may touch
+    guard = dst.clone()
+    B.tensair_stream_probe(dst, src, 4 * n, 2)
+    torch.cuda.synchronize()
+    blocks = min((n // 4 + 255) // 256, 256 * 64)
+    assert torch.equal(dst[4 * blocks:], guard[4 * blocks:])
+    with pytest.raises(B.TensairError):
+        B.tensair_stream_probe(dst, src, 4 * n, 9)
 
 
 # ------------------------------------------------------------------ error paths
