@@ -60,6 +60,10 @@ def main():
     ap.add_argument("--peer-payload", choices=["f32", "bf16"], default="f32",
                     help="f32: the peers' gradients as the paper sends them (the metric); bf16: as bfloat16 messages "
                          "(tensair_grad_pack / tensair_step_packed, a variant)")
+    ap.add_argument("--dim", type=int, default=None, help="other shapes: the named workload with this D (a multiple of 4)")
+    ap.add_argument("--table-dtype", choices=["f32", "bf16"], default=None, help="other shapes: element type of the tables")
+    ap.add_argument("--batch-centers", type=int, default=None, help="other shapes: centers per mini-batch")
+    ap.add_argument("--peers", type=int, default=None, help="other shapes: peer gradients per step (K)")
     ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine", "grad_pack"], default="step",
                     help="step: the worker step (the metric); the others time one of the further operations on its own")
     args = ap.parse_args()
@@ -77,6 +81,12 @@ def main():
     cfg = W.CONFIGS[args.config]
     if args.stochastic_rounding or args.resample_negatives:
         cfg = cfg.scaled(stochastic_rounding=args.stochastic_rounding, resample=args.resample_negatives)
+    other = {k: v for k, v in (("dim", args.dim), ("dtype", args.table_dtype), ("batch", args.batch_centers),
+                               ("peers", args.peers)) if v is not None}
+    if other:   # not the workload the metric is quoted on: the name in the output line says so
+        if args.peers == 0:
+            other["max_stale"] = 0
+        cfg = cfg.scaled(name=cfg.name + "+" + "+".join(f"{k}={v}" for k, v in other.items() if k != "max_stale"), **other)
     if args.steps is None:
         args.steps = {1: 100, 2: 50, 3: 20, 4: 10, 5: 6}[cfg.idx]   # bounded by the HBM the stored peers take
     if args.warmup is None:

@@ -241,6 +241,178 @@ k_apply(ApplyArgs a, int nblocks)
     }
 }
 
+// The same update for rows of at most 32 chunks (D <= 128): a whole wave per row would leave most of its
+// lanes without a chunk, and the update's rate is set by the number of row loads a wave issues, not by their
+// width (measured at a million words, 7 peers: D = 128 at 4.1 TB/s, D = 32 at 1.5 TB/s against 5.9 TB/s at
+// D = 256 with whole-wave rows: 0.36 and 0.25 ms per update, 0.31 and 0.09 ms with this kernel).  Here a wave updates 64/SUB rows at a time, one per group of SUB lanes: each pass takes the next
+// rows of the wave's share that any source has, the lanes that hold the sources' (start, mask) hand every
+// group its row's positions through lane shuffles, and a group walks its own row's sources, four loads in
+// flight, in source order -- every row is summed exactly as in k_apply.  Gradient messages in bfloat16
+// (PACKED) stay with k_apply.
+#ifndef APPLY_SUB_ROWS
+#define APPLY_SUB_ROWS 4   // rows per group of lanes and wave
+#endif
+template <typename T, int SUB, bool STREAM>
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(1, APPLY_MAX_WAVES)))
+k_apply_sub(ApplyArgs a, int nblocks)
+{
+    constexpr int RPW = WAVE / SUB;   // rows in one pass of a wave
+    constexpr int G = (APPLY_SUB_ROWS * RPW > 32) ? 32 : APPLY_SUB_ROWS * RPW;   // vocabulary rows per wave
+    constexpr int GPW = 64 / G;
+    int bid = blockIdx.x;
+    {
+        const int per_round = 8 * APPLY_CHUNK;
+        int full = (nblocks / per_round) * per_round;
+        if (bid < full) {
+            int round = bid / per_round, r = bid - round * per_round;
+            int xcd = r & 7, slot = r >> 3;
+            bid = round * per_round + xcd * APPLY_CHUNK + slot;
+        }
+    }
+    const int wave = uniform((int)(threadIdx.x >> 6)), lane = lane_id();
+    const int gw = bid * WAVES_PER_BLOCK + wave;
+    const int word = gw / GPW, sub = gw - word * GPW;
+    const int words = (int)((a.V + 63) >> 6);
+    if (word >= words) return;
+    const int ns = a.n_src;
+    const int C4 = a.D >> 2;
+    const int slot = lane / SUB, sl = lane - slot * SUB;   // group of the lane, chunk of the row it holds
+
+    // lane 32*tb + k: source k's rows inside this wave's share of table tb, as in k_apply
+    u32 m = 0, st = 0;
+    int U = 0;
+    u64 rows_ptr = 0;
+    {
+        const int tb = lane >> 5, k = lane & 31;
+        if (k < ns) {
+            const ApplySrc &s = a.src[tb][k];
+            if (s.ids != nullptr) {
+                const u64 mk = a.mask[tb][idx_at(words, k, word)];
+                const int lo = sub * G;
+                st = a.start[tb][idx_at(words, k, word)] + (u32)__popcll(mk & ((1ull << lo) - 1ull));
+                m = (u32)((mk >> lo) & ((1ull << G) - 1ull));
+                U = *s.n_rows;
+                if ((i64)U > s.capacity) U = (int)s.capacity;
+                rows_ptr = (u64)s.rows;
+            }
+        }
+    }
+    const int ptr_lo = (int)(u32)rows_ptr, ptr_hi = (int)(u32)(rows_ptr >> 32);
+    const float neg_lr = -a.lr;
+    const i64 row0 = (i64)word * 64 + sub * G;
+
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const bool mine = (lane >> 5) == tb;
+        u32 um = (u32)uniform((int)wave_or(mine ? m : 0u));
+        T *table = (T *)a.table[tb];
+        while (um) {
+            // the next RPW rows: lane 32*tb + k works out source k's position of each, group s keeps row s
+            int pos_s[RPW];
+            u32 S_my = 0;
+            int b_my = -1;
+#pragma unroll
+            for (int s = 0; s < RPW; ++s) {
+                pos_s[s] = 0;
+                if (um) {
+                    const int b = (int)__builtin_ctz(um);
+                    um &= um - 1u;
+                    if (row0 + b >= a.V) {   // only reachable with a corrupt index (flagged input)
+                        um = 0;
+                    } else {
+                        const u32 pos = st + (u32)__popc(m & ((1u << b) - 1u));
+                        const bool ok = mine && ((m >> b) & 1u) && (pos < (u32)U);
+                        const u64 S = __ballot(ok);
+                        pos_s[s] = (int)pos;
+                        if (slot == s) {
+                            S_my = (u32)(S >> (32 * tb));
+                            b_my = b;
+                        }
+                    }
+                }
+            }
+            const bool act = (b_my >= 0) && (sl < C4);
+            const i64 r = row0 + (b_my >= 0 ? b_my : 0);
+            T *wrow = table + (size_t)r * a.stride;
+            T *wp = wrow + 4 * sl;
+            typename Raw4<T>::type wraw;
+            zero_raw(wraw);
+            bool around = STREAM;
+            if (STREAM) {   // a 128-byte line shared with the neighbouring rows goes through the caches
+                const uintptr_t lo = (uintptr_t)wrow, hi = lo + (size_t)C4 * 4 * sizeof(T);
+                const uintptr_t line = (uintptr_t)wp & ~(uintptr_t)127;
+                around = line >= lo && line + 128 <= hi;
+            }
+            if (act) {
+                if (around) wraw = ldraw_s(wp);
+                else wraw = ldraw(wp);
+            }
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            u32 S_it = S_my;
+            while (__ballot(S_it != 0u)) {
+                float4 x[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool valid = S_it != 0u;
+                    const int k = valid ? (int)__builtin_ctz(S_it) : 0;
+                    S_it &= S_it - 1u;
+                    const int from = 32 * tb + k;
+                    int pos = 0;
+#pragma unroll
+                    for (int s = 0; s < RPW; ++s) {
+                        const int v = __shfl(pos_s[s], from, WAVE);
+                        pos = (slot == s) ? v : pos;
+                    }
+                    const u64 ptr = ((u64)(u32)__shfl(ptr_hi, from, WAVE) << 32) | (u64)(u32)__shfl(ptr_lo, from, WAVE);
+                    x[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (valid && act) {
+                        const float *src = (const float *)ptr + (size_t)(u32)pos * a.D + 4 * sl;
+                        x[j] = STREAM ? ld4s(src) : ld4(src);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc.x += x[j].x;
+                    acc.y += x[j].y;
+                    acc.z += x[j].z;
+                    acc.w += x[j].w;
+                }
+            }
+            float4 w = widen4(wraw);
+            w.x = fmaf(neg_lr, acc.x, w.x);
+            w.y = fmaf(neg_lr, acc.y, w.y);
+            w.z = fmaf(neg_lr, acc.z, w.z);
+            w.w = fmaf(neg_lr, acc.w, w.w);
+            if (!act) continue;
+            if constexpr (sizeof(T) == 2) {
+                if (a.sr) {   // the variant: the same draw per element as in update_row
+                    const u64 blk = (u64)r * (u64)C4 + (u64)sl;
+                    const philox_out o = philox4x32_10((u32)blk, (u32)(blk >> 32), a.sr_serial, 0x53524E44u + (u32)tb,
+                                                       a.sr_k0, a.sr_k1);
+                    v2u p;
+                    p.x = sr_bf16(w.x, o.r0) | (sr_bf16(w.y, o.r1) << 16);
+                    p.y = sr_bf16(w.z, o.r2) | (sr_bf16(w.w, o.r3) << 16);
+                    if (STREAM) __builtin_nontemporal_store(p, (GLOBAL_AS v2u *)wp);
+                    else *reinterpret_cast<v2u *>(wp) = p;
+                    continue;
+                }
+            }
+            if (STREAM) st4s(wp, w);
+            else st4(wp, w);
+        }
+    }
+}
+
+template <typename T, int SUB, bool STREAM>
+static void launch_apply_sub(const ApplyArgs &a, hipStream_t st)
+{
+    const int words = (int)((a.V + 63) >> 6);
+    constexpr int G = (APPLY_SUB_ROWS * (WAVE / SUB) > 32) ? 32 : APPLY_SUB_ROWS * (WAVE / SUB);
+    const i64 nwaves = (i64)words * (64 / G);
+    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    hipLaunchKernelGGL((k_apply_sub<T, SUB, STREAM>), dim3(nblocks), dim3(BLOCK), 0, st, a, nblocks);
+}
+
 template <typename T, bool STREAM, bool PACKED>
 static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
 {
@@ -260,8 +432,12 @@ static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
 template <typename T, bool STREAM>
 static void launch_apply_p(const ApplyArgs &a, hipStream_t st)
 {
+    const int C4 = a.D / 4;
     if (a.packed) launch_apply_t<T, STREAM, true>(a, st);
-    else launch_apply_t<T, STREAM, false>(a, st);
+    else if (C4 > 32) launch_apply_t<T, STREAM, false>(a, st);
+    else if (C4 > 16) launch_apply_sub<T, 32, STREAM>(a, st);
+    else if (C4 > 8) launch_apply_sub<T, 16, STREAM>(a, st);
+    else launch_apply_sub<T, 8, STREAM>(a, st);
 }
 
 static int index_blocks_for(const ApplyArgs &a, int k_begin, int k_end)
