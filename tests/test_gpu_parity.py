@@ -392,7 +392,7 @@ def _stream(cfg):
     return _stream_cached(cfg.vocab, cfg.zipf_s, cfg.tokens, cfg.stream_seed)
 
 
-def _run_both(cfg, steps, threads=8, prefetch=True, bf16_messages=False, loose_bf16_chain=False,
+def _run_both(cfg, steps, threads=16, prefetch=True, bf16_messages=False, loose_bf16_chain=False,
               pretrained=None, forced=False, min_moved=None):
     """The same worker steps on the GPU (DasgdWorker) and in the oracle (OracleWorker), compared step by step
     (own gradient, loss, peers' row ids) and at the end (tables).
