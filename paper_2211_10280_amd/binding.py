@@ -182,6 +182,11 @@ class GradBuffers:
         return ((self.in_ids[:ui].cpu().numpy(), self.in_rows[:ui].cpu().numpy()),
                 (self.out_ids[:uo].cpu().numpy(), self.out_rows[:uo].cpu().numpy()))
 
+    def ids_to_host(self):
+        """(ids_in, ids_out) as numpy arrays trimmed to n_rows (the rows stay on the device)."""
+        ui, uo = self.sizes()
+        return self.in_ids[:ui].cpu().numpy(), self.out_ids[:uo].cpu().numpy()
+
     def load(self, ids_in, rows_in, ids_out, rows_out):
         """Fill from host arrays (e.g. a gradient received from a peer)."""
         ui, uo = len(ids_in), len(ids_out)

@@ -392,6 +392,13 @@ def _stream(cfg):
     return _stream_cached(cfg.vocab, cfg.zipf_s, cfg.tokens, cfg.stream_seed)
 
 
+@functools.lru_cache(maxsize=1)
+def _oracle_init_tables(V, D, dtype, seed):
+    """The oracle's fresh model of a large configuration, made once for the tests that start from it (the
+    oracle fills two tables of 10^9 elements in a quarter of a minute)."""
+    return oracle.init_tables(V, D, D, oracle.F32 if dtype == "f32" else oracle.BF16, seed)
+
+
 def _run_both(cfg, steps, threads=16, prefetch=True, bf16_messages=False, loose_bf16_chain=False,
               pretrained=None, forced=False, min_moved=None):
     """The same worker steps on the GPU (DasgdWorker) and in the oracle (OracleWorker), compared step by step
@@ -420,6 +427,8 @@ def _run_both(cfg, steps, threads=16, prefetch=True, bf16_messages=False, loose_
             dev.append(t)
         dev = tuple(dev)
     gw = DasgdWorker(cfg, tok, counts, prefetch=prefetch, bf16_messages=bf16_messages, tables=dev)
+    if tables is None and cfg.vocab * cfg.dim >= 1 << 28:
+        tables = _oracle_init_tables(cfg.vocab, cfg.dim, cfg.dtype, cfg.seed)   # OracleWorker copies them
     ow = OracleWorker(cfg, tok, counts, threads=threads, bf16_messages=bf16_messages, tables=tables)
     w0 = (to_dev(ow.W_in), to_dev(ow.W_out))
     live = lambda: (gw.model.w_in[:, :D], gw.model.w_out[:, :D])        # the tables without their padding
@@ -452,7 +461,7 @@ def _run_both(cfg, steps, threads=16, prefetch=True, bf16_messages=False, loose_
         # peers: row ids bit-exact as well (they were computed on the GPU from the GPU's own snapshots)
         peer_side = gw.peer_bufs if cfg.grad_buffer == 1 else [p[0] for p in gw.peer_acc]
         for k, pg in enumerate(grads[1:]):
-            (pi, _), (po, _) = peer_side[k].to_host()
+            pi, po = peer_side[k].ids_to_host()
             assert np.array_equal(pi, pg.gin.ids) and np.array_equal(po, pg.gout.ids), f"step {t} peer {k + 1}"
         if cfg.grad_buffer > 1 and (t + 1) % cfg.grad_buffer == 0:
             # the buffer this worker broadcasts: the sum of its last grad_buffer gradients
