@@ -130,6 +130,31 @@ def test_sgns_grad_parity_with_resampled_negatives(case):
     _grad_parity(case, resample=True)
 
 
+def _random_grad_cases(n, seed):
+    """Seeded shapes: narrow to wide rows, windows 1..6, 0..12 negatives, batches from one center up, streams
+    from flat to steep, vocabularies from two words up, batches at the start, inside and at the end of the
+    stream."""
+    rng = np.random.default_rng(seed)
+    dims = [4, 8, 16, 36, 64, 100, 128, 132, 256, 260, 300, 384, 516, 1024]
+    out = []
+    for i in range(n):
+        D = dims[(i * 5 + int(rng.integers(0, 2))) % len(dims)]
+        V = int(rng.choice([2, 7, 100, 1500, 30_000, 70_000]))
+        T = int(rng.integers(50, 6000))
+        w, N = int(rng.integers(1, 7)), int(rng.integers(0, 13))
+        Bc = int(rng.integers(1, max(2, min(T, 60_000 // (D // 4 + 8)))))
+        Bc = min(Bc, T)
+        begin = int(rng.choice([0, T - Bc, int(rng.integers(0, T - Bc + 1))]))
+        out.append((V, D, D + 4 * int(rng.integers(0, 3)), T, float(rng.choice([0.6, 1.0, 1.4])), w, N, Bc, begin,
+                    "bf16" if rng.integers(0, 2) else "f32"))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_grad_cases(24, 2211_10280), ids=lambda c: "-".join(str(x) for x in c))
+def test_sgns_grad_parity_random_shapes(case):
+    _grad_parity(case)
+
+
 def _grad_parity(case, resample=False):
     V, D, stride, T, zs, w, N, Bc, begin, dtype = case
     _say("grad case", case, "resampled negatives" if resample else "")
@@ -233,6 +258,32 @@ def _rand_sparse(rng, V, D, U):
                                               # that do not end on cache-line borders, and rows padded to them
                                               (1_000_003, 300, 300, 2, True), (1_000_003, 300, 320, 2, True)])
 def test_dasgd_apply_parity(dtype, V, D, stride, K, own):
+    _apply_parity(dtype, V, D, stride, K, own)
+
+
+def _random_apply_shapes(n, seed):
+    """Seeded shapes off the beaten track: every lane grouping of the table update (D <= 32, <= 64, <= 128, one to
+    four chunk passes of a whole wave), dimensions just below and above the borders between them, padded and
+    dense rows, vocabularies that end inside a 64-row word, 0 to 15 peers."""
+    rng = np.random.default_rng(seed)
+    dims = [4, 8, 28, 32, 36, 60, 64, 68, 100, 124, 128, 132, 200, 252, 256, 260, 300, 508, 516, 768, 772, 1020, 1024]
+    out = []
+    for i in range(n):
+        D = dims[(i * 7 + int(rng.integers(0, 3))) % len(dims)]
+        V = int(rng.choice([1, 2, 63, 64, 65, 127, 500, 1000, 4097, 6001]))
+        stride = D + 4 * int(rng.integers(0, 3))
+        K = int(rng.integers(0, 16))
+        out.append(("bf16" if rng.integers(0, 2) else "f32", V, D, stride, K, bool(rng.integers(0, 4))))
+    return out
+
+
+@pytest.mark.parametrize("dtype,V,D,stride,K,own", _random_apply_shapes(28, 20221118),
+                         ids=lambda v: str(v))
+def test_dasgd_apply_parity_random_shapes(dtype, V, D, stride, K, own):
+    _apply_parity(dtype, V, D, stride, K, own)
+
+
+def _apply_parity(dtype, V, D, stride, K, own):
     _say("apply", dtype, V, D, stride, K, own)
     bd, od, _, _ = DT[dtype]
     rng = np.random.default_rng(V * 31 + K)
