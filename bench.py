@@ -176,7 +176,7 @@ def main():
     # HBM traffic of the dominant kernel: not measured by this run (that takes hardware counters, i.e. rocprofv3
     # around the whole process) but read from the stored summary of such runs on this workload, and said so
     traffic = traffic_source = trace_avg_ms = None
-    tname = f"traffic_{cfg.name}{'_bf16_messages' if peer_elem == 2 else ''}.json"
+    tname = f"traffic_{cfg.name.replace('+', '_').replace('=', '')}{'_bf16_messages' if peer_elem == 2 else ''}.json"
     tpath = os.path.join(ROOT, "profiles", tname)
     if os.path.exists(tpath):
         try:
