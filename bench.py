@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--table-dtype", choices=["f32", "bf16"], default=None, help="other shapes: element type of the tables")
     ap.add_argument("--batch-centers", type=int, default=None, help="other shapes: centers per mini-batch")
     ap.add_argument("--peers", type=int, default=None, help="other shapes: peer gradients per step (K)")
+    ap.add_argument("--vocab", type=int, default=None, help="other shapes: vocabulary size V")
     ap.add_argument("--op", choices=["step", "grad_add", "dense_apply", "lookup", "cosine", "grad_pack"], default="step",
                     help="step: the worker step (the metric); the others time one of the further operations on its own")
     args = ap.parse_args()
@@ -82,7 +83,7 @@ def main():
     if args.stochastic_rounding or args.resample_negatives:
         cfg = cfg.scaled(stochastic_rounding=args.stochastic_rounding, resample=args.resample_negatives)
     other = {k: v for k, v in (("dim", args.dim), ("dtype", args.table_dtype), ("batch", args.batch_centers),
-                               ("peers", args.peers)) if v is not None}
+                               ("peers", args.peers), ("vocab", args.vocab)) if v is not None}
     if other:   # not the workload the metric is quoted on: the name in the output line says so
         if args.peers == 0:
             other["max_stale"] = 0

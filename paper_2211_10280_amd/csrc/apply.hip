@@ -51,6 +51,9 @@ __global__ void __launch_bounds__(BLOCK) k_apply_index(ApplyArgs a, int k0)
 #ifndef APPLY_G
 #define APPLY_G 4   // vocabulary rows per wave (measured: 16 -> 4 rows gains 4 %)
 #endif
+#ifndef APPLY_G_SPARSE
+#define APPLY_G_SPARSE 16   // the same where few of the vocabulary's rows are touched
+#endif
 
 // Stochastic rounding of one fp32 value to bfloat16: 16 random bits are added below the bfloat16 mantissa
 // and the sum is truncated, so the value goes up with probability (discarded bits)/2^16; infinities and
@@ -413,20 +416,35 @@ static void launch_apply_sub(const ApplyArgs &a, hipStream_t st)
     hipLaunchKernelGGL((k_apply_sub<T, SUB, STREAM>), dim3(nblocks), dim3(BLOCK), 0, st, a, nblocks);
 }
 
-template <typename T, bool STREAM, bool PACKED>
-static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
+template <typename T, int G, bool STREAM, bool PACKED>
+static void launch_apply_g(const ApplyArgs &a, hipStream_t st)
 {
     const int iters = (a.D / 4 + WAVE - 1) / WAVE;
     const int words = (int)((a.V + 63) >> 6);
-    const i64 nwaves = (i64)words * (64 / APPLY_G);
+    const i64 nwaves = (i64)words * (64 / G);
     const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     dim3 grid(nblocks), blk(BLOCK);
     switch (iters) {
-    case 1: hipLaunchKernelGGL((k_apply<T, 1, APPLY_G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
-    case 2: hipLaunchKernelGGL((k_apply<T, 2, APPLY_G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
-    case 3: hipLaunchKernelGGL((k_apply<T, 3, APPLY_G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
-    default: hipLaunchKernelGGL((k_apply<T, 4, APPLY_G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
+    case 1: hipLaunchKernelGGL((k_apply<T, 1, G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
+    case 2: hipLaunchKernelGGL((k_apply<T, 2, G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
+    case 3: hipLaunchKernelGGL((k_apply<T, 3, G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
+    default: hipLaunchKernelGGL((k_apply<T, 4, G, STREAM, PACKED>), grid, blk, 0, st, a, nblocks); break;
     }
+}
+
+// Rows per wave.  Where most vocabulary rows are touched, 4 rows per wave are best (16: -4 % at a million words and
+// 7 peers, two thirds of the rows touched); where few are, most waves of such a grid find nothing, and 16 rows per
+// wave win (same gradients, update at 2 / 4 / 8 million words: 0.85 / 1.11 / 1.49 ms with 4 rows, 0.86 / 1.01 / 1.16 ms
+// with 16, 64 rows no better).  How many rows the union has is only known on the device; the sources' capacities
+// bound it, and below three quarters of a row of capacity per vocabulary row the sparse shape is taken.
+template <typename T, bool STREAM, bool PACKED>
+static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
+{
+    i64 cap = 0;
+    for (int k = 0; k < a.n_src; ++k)
+        if (a.src[1][k].ids != nullptr) cap += a.src[1][k].capacity;
+    if (4 * cap < 3 * a.V) launch_apply_g<T, APPLY_G_SPARSE, STREAM, PACKED>(a, st);
+    else launch_apply_g<T, APPLY_G, STREAM, PACKED>(a, st);
 }
 
 template <typename T, bool STREAM>

@@ -261,6 +261,15 @@ def test_dasgd_apply_parity(dtype, V, D, stride, K, own):
     _apply_parity(dtype, V, D, stride, K, own)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,D,stride,K", [(70_001, 300, 320, 3), (20_011, 512, 512, 15), (4099, 132, 132, 0),
+                                          (300_007, 1024, 1024, 1)])
+def test_dasgd_apply_parity_few_rows_of_a_large_vocabulary(dtype, V, D, stride, K):
+    """Gradients that touch a few per cent of the vocabulary: the update then runs in its shape for sparse
+    unions (more vocabulary rows per wave)."""
+    _apply_parity(dtype, V, D, stride, K, True, thin=40)
+
+
 def _random_apply_shapes(n, seed):
     """Seeded shapes off the beaten track: every lane grouping of the table update (D <= 32, <= 64, <= 128, one to
     four chunk passes of a whole wave), dimensions just below and above the borders between them, padded and
@@ -283,8 +292,8 @@ def test_dasgd_apply_parity_random_shapes(dtype, V, D, stride, K, own):
     _apply_parity(dtype, V, D, stride, K, own)
 
 
-def _apply_parity(dtype, V, D, stride, K, own):
-    _say("apply", dtype, V, D, stride, K, own)
+def _apply_parity(dtype, V, D, stride, K, own, thin=1):
+    _say("apply", dtype, V, D, stride, K, own, f"sizes / {thin}")
     bd, od, _, _ = DT[dtype]
     rng = np.random.default_rng(V * 31 + K)
     Wi, Wo = _random_tables(V, D, stride, dtype, seed=K + 1)
@@ -295,6 +304,8 @@ def _apply_parity(dtype, V, D, stride, K, own):
         # mix of sizes: empty, single row, dense, first/last row of the vocabulary
         Ui = [0, 1, V // 7, V // 2, V][k % 5] if k else max(V // 3, 1)
         Uo = [V, V // 2, 1, 0, V // 5][k % 5] if k else max(V // 4, 1)
+        if thin > 1:
+            Ui, Uo = (Ui + thin - 1) // thin, (Uo + thin - 1) // thin
         si, so = _rand_sparse(rng, V, D, Ui), _rand_sparse(rng, V, D, Uo)
         gb = B.GradBuffers(max(Ui, 1) + 3, max(Uo, 1) + 5, D)
         gb.load(si[0], si[1], so[0], so[1])
@@ -889,26 +900,28 @@ def test_grad_pack_errors():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("V,D,stride,K,own", [(1000, 32, 32, 1, True), (4099, 300, 304, 7, True),
-                                              (513, 512, 512, 31, True), (2000, 64, 64, 4, False),
-                                              (70, 1024, 1024, 2, True), (1_000_003, 300, 300, 3, True)])
-def test_dasgd_apply_packed_parity(dtype, V, D, stride, K, own):
+@pytest.mark.parametrize("V,D,stride,K,own,thin", [(1000, 32, 32, 1, True, 1), (4099, 300, 304, 7, True, 1),
+                                              (513, 512, 512, 31, True, 1), (2000, 64, 64, 4, False, 1),
+                                              (70, 1024, 1024, 2, True, 1), (1_000_003, 300, 300, 3, True, 1),
+                                              # a few per cent of the rows touched: the shape for sparse unions
+                                              (70_001, 300, 320, 7, True, 40), (20_011, 64, 64, 3, True, 40)])
+def test_dasgd_apply_packed_parity(dtype, V, D, stride, K, own, thin):
     """Eq. 1 with the peers' gradients given as bfloat16 messages (the same bits on both sides), the own
     gradient in fp32."""
-    _say("apply packed", dtype, V, D, stride, K, own)
+    _say("apply packed", dtype, V, D, stride, K, own, f"sizes / {thin}")
     bd, od, _, _ = DT[dtype]
     rng = np.random.default_rng(V * 17 + K)
     Wi, Wo = _random_tables(V, D, stride, dtype, seed=K + 5)
     d_in, d_out = _tables_to_dev(Wi, dtype), _tables_to_dev(Wo, dtype)
     m = B.Model(V, D, bd, 2, 3, 64, K, 1, np.ones(V, np.uint64), row_stride=stride, tables=(d_in, d_out))
-    Ui, Uo = max(V // 3, 1), max(V // 4, 1)
+    Ui, Uo = max(V // 3 // thin, 1), max(V // 4 // thin, 1)
     si, so = _rand_sparse(rng, V, D, Ui), _rand_sparse(rng, V, D, Uo)
     own_buf = B.GradBuffers(Ui + 3, Uo + 5, D)
     own_buf.load(si[0], si[1], so[0], so[1])
     srcs_in, srcs_out, msgs = [si], [so], []
     for k in range(1, K + 1):
-        Ui = [0, 1, V // 7, V // 2, V][k % 5]
-        Uo = [V, V // 2, 1, 0, V // 5][k % 5]
+        Ui = ([0, 1, V // 7, V // 2, V][k % 5] + thin - 1) // thin
+        Uo = ([V, V // 2, 1, 0, V // 5][k % 5] + thin - 1) // thin
         pi, po = _rand_sparse(rng, V, D, Ui), _rand_sparse(rng, V, D, Uo)
         bi, bo = oracle.grad_pack_rows(pi[1]), oracle.grad_pack_rows(po[1])
         msg = B.PackedBuffers(max(Ui, 1) + 3, max(Uo, 1) + 5, D)
