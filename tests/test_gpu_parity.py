@@ -111,6 +111,11 @@ GRAD_CASES = [
     (900, 772, 776, 6_000, 1.0, 2, 3, 96, 40, "f32"),           # three + a tail of 4, padded stride
     (900, 320, 320, 6_000, 1.0, 2, 3, 96, 40, "f32"),           # one + a full tail of 64
     (5_000_000, 8, 8, 50_000, 0.8, 4, 6, 2048, 3000, "f32"),    # 23 key bits: three radix passes
+    # a steep word distribution over few words and 2^18 occurrences and more: long rows on both sides, with
+    # rows held as one register set + tail at a padded stride, in bf16, and as two register sets + tail
+    (150, 300, 320, 30_000, 1.5, 8, 15, 1024, 512, "f32"),
+    (150, 512, 512, 30_000, 1.4, 8, 15, 1100, 300, "bf16"),
+    (5000, 520, 520, 30_000, 1.5, 8, 15, 1024, 100, "f32"),
 ]
 
 
