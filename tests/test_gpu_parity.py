@@ -1170,6 +1170,38 @@ def test_training_with_and_without_prefetch_is_bit_identical(name, idx, kw):
     b.model.close()
 
 
+def _same_on_device(a, b):
+    """Own gradient and loss of two workers, compared where they are."""
+    (ai, ao), (bi, bo) = a.own.sizes(), b.own.sizes()
+    return ((ai, ao) == (bi, bo) and torch.equal(a.own.in_ids[:ai], b.own.in_ids[:bi])
+            and torch.equal(a.own.out_ids[:ao], b.own.out_ids[:bo])
+            and torch.equal(a.own.in_rows[:ai], b.own.in_rows[:bi])
+            and torch.equal(a.own.out_rows[:ao], b.own.out_rows[:bo]) and torch.equal(a.mean_loss, b.mean_loss))
+
+
+@pytest.mark.parametrize("idx,steps", [(1, 500), (2, 1000), (3, 200), (4, 60), (5, 16)])
+def test_long_runs_with_and_without_prefetch_are_bit_identical(idx, steps):
+    """The full-size configurations for many steps, two workers side by side on one stream: one announces every
+    coming mini-batch (preparation on the library's second stream: under the table update, beside the forward
+    pass, or left to the consuming call, as the configuration has it; index jobs riding in other launches, two
+    sets of masks and workspaces taking turns), the other does not.  Anything that ran before what it depends
+    on had finished would show as a difference in some step's gradient or in the final tables."""
+    cfg = W.CONFIGS[idx]
+    tok, counts = _stream(cfg)
+    a = DasgdWorker(cfg, tok, counts, prefetch=True)
+    b = DasgdWorker(cfg, tok, counts, prefetch=False)
+    for t in range(steps):
+        a.step(want_loss=True)
+        b.step(want_loss=True)
+        if t % 5 == 4 or t == steps - 1:
+            assert _same_on_device(a, b), f"step {t}"
+    a.model.status()
+    b.model.status()
+    assert torch.equal(a.model.w_in, b.model.w_in) and torch.equal(a.model.w_out, b.model.w_out)
+    a.model.close()
+    b.model.close()
+
+
 # ------------------------------------------------------------------ measurement aids
 def test_streaming_probes_move_what_they_say():
     """The probes behind the bandwidth ceilings of the benchmark line: both copies reproduce their source, the
