@@ -1202,6 +1202,29 @@ def test_long_runs_with_and_without_prefetch_are_bit_identical(idx, steps):
     b.model.close()
 
 
+@pytest.mark.parametrize("idx,steps,kw,bf16_messages", [
+    (3, 60, {}, True), (5, 12, {}, True), (3, 61, dict(grad_buffer=3), False), (3, 40, dict(grad_buffer=2), True),
+    (5, 12, dict(stochastic_rounding=True), False), (4, 30, dict(resample=True), False),
+], ids=["cfg3_msg", "cfg5_msg", "cfg3_buffer3", "cfg3_buffer2_msg", "cfg5_stochastic", "cfg4_resample"])
+def test_long_runs_of_the_variants_with_and_without_prefetch_are_bit_identical(idx, steps, kw, bf16_messages):
+    """The same for the variants: gradients as bfloat16 messages, maxGradBuffer above one (with and without
+    messages), stochastic rounding of bf16 tables, redrawn negatives."""
+    cfg = W.CONFIGS[idx].scaled(**kw) if kw else W.CONFIGS[idx]
+    tok, counts = _stream(cfg)
+    a = DasgdWorker(cfg, tok, counts, prefetch=True, bf16_messages=bf16_messages)
+    b = DasgdWorker(cfg, tok, counts, prefetch=False, bf16_messages=bf16_messages)
+    for t in range(steps):
+        a.step(want_loss=True)
+        b.step(want_loss=True)
+        if t % 5 == 4 or t == steps - 1:
+            assert _same_on_device(a, b), f"step {t}"
+    a.model.status()
+    b.model.status()
+    assert torch.equal(a.model.w_in, b.model.w_in) and torch.equal(a.model.w_out, b.model.w_out)
+    a.model.close()
+    b.model.close()
+
+
 # ------------------------------------------------------------------ measurement aids
 def test_streaming_probes_move_what_they_say():
     """The probes behind the bandwidth ceilings of the benchmark line: both copies reproduce their source, the
