@@ -255,12 +255,12 @@ k_apply(ApplyArgs a, int nblocks)
 #ifndef APPLY_SUB_ROWS
 #define APPLY_SUB_ROWS 4   // rows per group of lanes and wave
 #endif
-template <typename T, int SUB, bool STREAM>
+template <typename T, int SUB, int ROWS, bool STREAM>
 __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(1, APPLY_MAX_WAVES)))
 k_apply_sub(ApplyArgs a, int nblocks)
 {
     constexpr int RPW = WAVE / SUB;   // rows in one pass of a wave
-    constexpr int G = (APPLY_SUB_ROWS * RPW > 32) ? 32 : APPLY_SUB_ROWS * RPW;   // vocabulary rows per wave
+    constexpr int G = (ROWS * RPW > 32) ? 32 : ROWS * RPW;   // vocabulary rows per wave
     constexpr int GPW = 64 / G;
     int bid = blockIdx.x;
     {
@@ -406,14 +406,32 @@ k_apply_sub(ApplyArgs a, int nblocks)
     }
 }
 
+template <typename T, int SUB, int ROWS, bool STREAM>
+static void launch_apply_sub_r(const ApplyArgs &a, hipStream_t st)
+{
+    const int words = (int)((a.V + 63) >> 6);
+    constexpr int G = (ROWS * (WAVE / SUB) > 32) ? 32 : ROWS * (WAVE / SUB);
+    const i64 nwaves = (i64)words * (64 / G);
+    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    hipLaunchKernelGGL((k_apply_sub<T, SUB, ROWS, STREAM>), dim3(nblocks), dim3(BLOCK), 0, st, a, nblocks);
+}
+
+// few of the vocabulary's rows touched, going by the sources' capacities (see launch_apply_t)
+static bool sparse_union(const ApplyArgs &a)
+{
+    i64 cap = 0;
+    for (int k = 0; k < a.n_src; ++k)
+        if (a.src[1][k].ids != nullptr) cap += a.src[1][k].capacity;
+    return 4 * cap < 3 * a.V;
+}
+
+// 4 rows per group of lanes and wave, or 32 rows per wave where few rows are touched (8 M words, D = 128, bf16:
+// update 0.67 -> 0.42 ms; 16 M words, D = 64: 0.58 -> 0.40 ms)
 template <typename T, int SUB, bool STREAM>
 static void launch_apply_sub(const ApplyArgs &a, hipStream_t st)
 {
-    const int words = (int)((a.V + 63) >> 6);
-    constexpr int G = (APPLY_SUB_ROWS * (WAVE / SUB) > 32) ? 32 : APPLY_SUB_ROWS * (WAVE / SUB);
-    const i64 nwaves = (i64)words * (64 / G);
-    const int nblocks = (int)((nwaves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-    hipLaunchKernelGGL((k_apply_sub<T, SUB, STREAM>), dim3(nblocks), dim3(BLOCK), 0, st, a, nblocks);
+    if (SUB > 8 && sparse_union(a)) launch_apply_sub_r<T, SUB, 16, STREAM>(a, st);
+    else launch_apply_sub_r<T, SUB, APPLY_SUB_ROWS, STREAM>(a, st);
 }
 
 template <typename T, int G, bool STREAM, bool PACKED>
@@ -440,10 +458,7 @@ static void launch_apply_g(const ApplyArgs &a, hipStream_t st)
 template <typename T, bool STREAM, bool PACKED>
 static void launch_apply_t(const ApplyArgs &a, hipStream_t st)
 {
-    i64 cap = 0;
-    for (int k = 0; k < a.n_src; ++k)
-        if (a.src[1][k].ids != nullptr) cap += a.src[1][k].capacity;
-    if (4 * cap < 3 * a.V) launch_apply_g<T, APPLY_G_SPARSE, STREAM, PACKED>(a, st);
+    if (sparse_union(a)) launch_apply_g<T, APPLY_G_SPARSE, STREAM, PACKED>(a, st);
     else launch_apply_g<T, APPLY_G, STREAM, PACKED>(a, st);
 }
 

@@ -268,7 +268,10 @@ def test_dasgd_apply_parity(dtype, V, D, stride, K, own):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("V,D,stride,K", [(70_001, 300, 320, 3), (20_011, 512, 512, 15), (4099, 132, 132, 0),
-                                          (300_007, 1024, 1024, 1)])
+                                          (300_007, 1024, 1024, 1),
+                                          # rows of at most 32 chunks: groups of 32 and of 16 lanes
+                                          (70_001, 128, 128, 7), (50_000, 100, 104, 15), (20_011, 64, 64, 3),
+                                          (30_000, 36, 36, 1)])
 def test_dasgd_apply_parity_few_rows_of_a_large_vocabulary(dtype, V, D, stride, K):
     """Gradients that touch a few per cent of the vocabulary: the update then runs in its shape for sparse
     unions (more vocabulary rows per wave)."""
