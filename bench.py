@@ -18,7 +18,8 @@ Procedure
      same timed region;
   5. the CPU oracle is timed on the host for a bounded sample (one step's own gradient + apply).
 
-Prints one JSON line.
+Prints one JSON line.  --dim, --table-dtype, --batch-centers, --peers and --vocab run a modified copy of the chosen
+workload (named so in the line's config.workload): other shapes, not the workload the metric is quoted on.
 """
 from __future__ import annotations
 
