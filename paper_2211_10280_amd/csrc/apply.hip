@@ -247,14 +247,15 @@ k_apply(ApplyArgs a, int nblocks)
     }
 }
 
-// The same update for rows of at most 32 chunks (D <= 128): a whole wave per row would leave most of its
-// lanes without a chunk, and the update's rate is set by the number of row loads a wave issues, not by their
-// width (measured at a million words, 7 peers: D = 128 at 4.1 TB/s, D = 32 at 1.5 TB/s against 5.9 TB/s at
-// D = 256 with whole-wave rows: 0.36 and 0.25 ms per update, 0.31 and 0.09 ms with this kernel).  Here a wave updates 64/SUB rows at a time, one per group of SUB lanes: each pass takes the next
-// rows of the wave's share that any source has, the lanes that hold the sources' (start, mask) hand every
-// group its row's positions through lane shuffles, and a group walks its own row's sources, four loads in
-// flight, in source order -- every row is summed exactly as in k_apply.  Gradient messages in bfloat16
-// (PACKED) stay with k_apply.
+// The same update for rows of at most 32 chunks (D <= 128).  A whole wave per row would leave most of its lanes
+// without a chunk, and the update's rate follows the number of row loads a wave issues, not their width
+// (measured at a million words and 7 peers with whole-wave rows: 4.1 TB/s at D = 128 and 1.5 TB/s at D = 32 against
+// 5.9 TB/s at D = 256; update 0.36 and 0.25 ms, with this kernel 0.31 and 0.09 ms).  Here a wave updates 64/SUB
+// rows at a time, one per group of SUB lanes: each pass takes the next rows of the wave's share that any source
+// has, the lanes that hold the sources' (start, mask) hand every group its row's positions through lane
+// shuffles, and a group walks its own row's sources, four loads in flight, in source order -- every row is
+// summed exactly as in k_apply.  ROWS: vocabulary rows per group and wave (more where few rows are touched, see
+// launch_apply_sub).  Gradient messages in bfloat16 (PACKED) stay with k_apply.
 #ifndef APPLY_SUB_ROWS
 #define APPLY_SUB_ROWS 4   // rows per group of lanes and wave
 #endif
