@@ -21,6 +21,9 @@
 #ifndef SEG_UNROLL
 #define SEG_UNROLL 4
 #endif
+#ifndef SEG_RUNS
+#define SEG_RUNS 1
+#endif
 
 // ---------------------------------------------------------------- forward
 // A row of D elements held by one wave.  NQ float4 registers per lane (lane l owns chunks l, l+64, ...,
@@ -398,6 +401,57 @@ __device__ __forceinline__ void segreduce_tile(const SegReduceArgs &a, int block
         else acc.template store<false>(dest == 1 ? part : part + a.D, a.D, lane);
     };
 
+    if constexpr (MODE == 0 && SEG_RUNS) {
+        // Runs.  The occurrences of one center position follow one another in the sorted list of a row, and
+        // where a word is frequent a position has many of them (the most frequent word of a steep distribution
+        // is drawn as a negative dozens of times per position): consecutive entries of a row that take the same
+        // center's row are one run, their scales are summed first (in a fixed order: a segmented scan across the
+        // lanes) and the row is fetched and added once, scaled by the sum.
+        const u64 rp = (u64)row_l;
+        const u32 up_lo = (u32)__shfl_up((int)(u32)rp, 1, WAVE), up_hi = (u32)__shfl_up((int)(u32)(rp >> 32), 1, WAVE);
+        const bool in_range = lane >= e_begin && lane < e_end;
+        const bool rh_l = in_range && (lane == e_begin || seg_l != seg_up || (u32)rp != up_lo || (u32)(rp >> 32) != up_hi);
+        const u64 rheads = __ballot(rh_l);
+        const u64 upto = rheads & ((lane == 63) ? ~0ull : ((2ull << lane) - 1ull));
+        const int my_head = (in_range && upto) ? 63 - (int)__builtin_clzll(upto) : lane;
+        float xs = in_range ? scale_l : 0.f;   // becomes the sum of the scales from the run's first entry to this one
+#pragma unroll
+        for (int o = 1; o < WAVE; o <<= 1) {
+            const float y = __shfl_up(xs, o, WAVE);
+            if (lane - o >= my_head) xs += y;
+        }
+        u64 rmask = rheads;
+        while (rmask) {
+            LoadedRow<T, NQ, TAIL> r[UNROLL];
+            float sc[UNROLL];
+            int hd[UNROLL];
+#pragma unroll
+            for (int x = 0; x < UNROLL; ++x) {
+                hd[x] = -1;
+                if (rmask) {
+                    const int h = (int)__builtin_ctzll(rmask);
+                    rmask &= rmask - 1ull;
+                    const int last = (rmask ? (int)__builtin_ctzll(rmask) : e_end) - 1;
+                    hd[x] = h;
+                    sc[x] = rd_lane(xs, last);
+                    r[x].load((const T *)rd_lane64(rp, h), a.D, lane);
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < UNROLL; ++x) {
+                if (hd[x] >= 0) {
+                    if (hd[x] != e_begin && ((heads >> hd[x]) & 1ull)) {   // a new row begins here
+                        flush();
+                        acc.zero();
+                        cur = rd_lane(seg_l, hd[x]);
+                        const int end = row_end(hd[x]);
+                        dest = ((end < 0) || (end - hd[x]) > TILE) ? 2 : 0;
+                    }
+                    acc.axpy(sc[x], r[x]);
+                }
+            }
+        }
+    } else
     for (int e0 = e_begin; e0 < e_end; e0 += UNROLL) {
         LoadedRow<T, NQ, TAIL> r[UNROLL];
         float sc[UNROLL];
